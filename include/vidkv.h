@@ -1,0 +1,150 @@
+/*
+ * vidkv.h - C ABI of the MI355X (gfx950) VidKV hot path:
+ *   sub-2-bit KV-cache codec + single-query GQA decode attention over the
+ *   packed cache.
+ *
+ * Method (arXiv 2503.16257): keys are quantized per channel with mixed
+ * precision - the n_anom channels of largest range get the 2-bit uniform
+ * group quantizer (Eq. 4), the rest get the FFT-based 1-bit quantizer (Eq. 5;
+ * Alg. 3); values get the per-channel ternary quantizer (Eq. 6; Alg. 2) with
+ * the most salient visual tokens (Sec. 3.3 (2)) preserved, here in fp16; one
+ * decode step computes Softmax(q K^T / sqrt(D)) V over the dequantized cache
+ * followed by the fp16 residual tokens (Eq. 3; Alg. 1, Decoding).
+ *
+ * General rules
+ *  - Every pointer named *_dev is DEVICE memory on the current HIP device;
+ *    `params` is HOST memory.  The caller owns every buffer; the library
+ *    allocates nothing, keeps no pointer after a call returns and never
+ *    synchronizes: all work is enqueued on `hip_stream` (a hipStream_t passed
+ *    as void*, NULL = the default stream).
+ *  - All arguments are checked on the host before anything is launched; a
+ *    failed check returns a status and launches nothing.  A launch failure
+ *    returns VIDKV_EHIP.  Nothing aborts or throws across this boundary.
+ *  - Tensors are dense, row-major, fp16 (IEEE binary16) unless stated.
+ *    Inputs must be finite; non-finite inputs give unspecified codes.
+ *  - Shapes: L = n_layers, B = batch, Hkv = n_kv_heads, Hq = n_q_heads
+ *    (Hq % Hkv == 0, Hq / Hkv <= 8; query head h reads KV head h / (Hq/Hkv)),
+ *    D = head_dim = 128, G = group = 32, Tq = t_quant (multiple of 32).
+ *  - The packed buffers are opaque to the caller; their byte sizes come from
+ *    the vidkv_packed_*_bytes functions.  Buffers must be 256-byte aligned.
+ */
+#ifndef VIDKV_H
+#define VIDKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define VIDKV_ABI_VERSION 1
+
+typedef enum {
+  VIDKV_OK = 0,
+  VIDKV_EINVAL = 1,   /* NULL pointer, bad enum, inconsistent arguments        */
+  VIDKV_ESHAPE = 2,   /* a dimension this build does not support               */
+  VIDKV_ENOSPACE = 3, /* an output or workspace buffer is too small            */
+  VIDKV_EHIP = 4      /* the HIP runtime reported an error at launch           */
+} vidkv_status;
+
+/* Hyper-parameters of Alg. 1-3 (G, k, p, gamma) and the cache geometry.
+ * Plain data, passed by pointer from host memory, never retained. */
+typedef struct vidkv_params {
+  int32_t n_layers;      /* L  >= 1                                             */
+  int32_t batch;         /* B  >= 1                                             */
+  int32_t n_kv_heads;    /* Hkv >= 1                                            */
+  int32_t n_q_heads;     /* Hq, multiple of Hkv, Hq/Hkv <= 8                    */
+  int32_t head_dim;      /* must be 128                                         */
+  int32_t group;         /* G, must be 32 (Sec. 4.1)                            */
+  int32_t t_quant;       /* Tq >= 0, multiple of 32: tokens held in packed form */
+  int32_t n_anom;        /* 2-bit key channels per head: 0..128, multiple of 8
+                            (k * D of Sec. 3.2 (1))                             */
+  int32_t use_fft;       /* must be 1: Eq. 5 path for the normal channels       */
+  int32_t n_salient;     /* protected value tokens per sequence, 0..Tq
+                            (n = p * l_v of Sec. 3.3 (2))                       */
+  float gamma;           /* ternary threshold factor of Eq. 6 (paper: 0.7)      */
+  float softmax_scale;   /* multiplies q.k before the softmax (1/sqrt(128))     */
+} vidkv_params;
+
+/* Size queries: pure host functions, usable without a GPU.  Return 0 when
+ * `params` is NULL or invalid.  `which`: 0 = quantize_keys, 1 = quantize_values,
+ * 2 = decode_attention. */
+size_t vidkv_packed_keys_bytes(const vidkv_params *params);
+size_t vidkv_packed_values_bytes(const vidkv_params *params);
+size_t vidkv_workspace_bytes(const vidkv_params *params, int which);
+
+/* Alg. 3 (MixQuant): per (layer, sequence, KV head) rank the 128 channels by
+ * range max-min over all Tq tokens (ties: lower channel first), code the top
+ * n_anom channels with Eq. 4 at 2 bits (z = min, s = (max-min)/3 per channel
+ * and 32-token group, round-half-even) and the others with Eq. 5: a 32-point
+ * DFT along the tokens of each group, one sign bit for each of the 17 real and
+ * 15 imaginary independent coefficients, and the mean |Re|, mean |Im| over the
+ * 32 bins as fp16 scales.
+ *   K_dev        in : [L, B, Hkv, Tq, 128] fp16
+ *   packed_K_dev out: >= vidkv_packed_keys_bytes(params) bytes
+ *   workspace_dev   : >= vidkv_workspace_bytes(params, 0) bytes, scratch     */
+vidkv_status vidkv_quantize_keys(const vidkv_params *params, const void *K_dev,
+                                 void *packed_K_dev, size_t packed_bytes,
+                                 void *workspace_dev, size_t workspace_bytes,
+                                 void *hip_stream);
+
+/* Alg. 2 (1.58Quant with token protection): per channel and 32-token group
+ * s = mean |V| over the unprotected tokens, code = +1 / -1 / 0 against
+ * +-gamma*s (Eq. 6); protected tokens are coded 0 and their rows copied
+ * verbatim.  The protected set is shared by all layers and heads of a
+ * sequence and is given either as scores (top n_salient, ties: lower index
+ * first; Eq. 7 scores are computed by the caller) or as an index list.
+ *   V_dev           in : [L, B, Hkv, Tq, 128] fp16
+ *   saliency_dev    in : [B, Tq] float32, or NULL
+ *   salient_idx_dev in : [B, n_salient] int32, strictly ascending per
+ *                        sequence, or NULL.  With n_salient > 0 exactly one of
+ *                        the two is non-NULL; with n_salient == 0 both are
+ *                        ignored.
+ *   packed_V_dev    out: >= vidkv_packed_values_bytes(params) bytes
+ *   workspace_dev      : >= vidkv_workspace_bytes(params, 1) bytes           */
+vidkv_status vidkv_quantize_values(const vidkv_params *params, const void *V_dev,
+                                   const float *saliency_dev,
+                                   const int32_t *salient_idx_dev,
+                                   void *packed_V_dev, size_t packed_bytes,
+                                   void *workspace_dev, size_t workspace_bytes,
+                                   void *hip_stream);
+
+/* Alg. 1, Decoding, for one layer: out = Softmax(scale * q [K'; K_r]^T) [V'; V_r]
+ * (Eq. 3) where K', V' are the dequantized packed tokens (never materialised
+ * in memory) and K_r, V_r the first tail_len[b] rows of the fp16 residual
+ * buffers.  Appending the new token to the residual buffers and advancing
+ * tail_len is the caller's job.
+ *   layer           : 0..L-1, selects the layer inside the packed buffers
+ *   q_dev        in : [B, Hq, 128] fp16
+ *   packed_K_dev, packed_V_dev in : as written by the two quantize calls with
+ *                     the same params
+ *   K_tail_dev, V_tail_dev in : [B, Hkv, tail_capacity, 128] fp16 of this
+ *                     layer; may be NULL when tail_capacity == 0
+ *   tail_len_dev in : [B] int32, each 0..tail_capacity; NULL means all zero
+ *   out_dev     out : [B, Hq, 128] fp16 (fp32 accumulation, RNE at the end)
+ *   workspace_dev   : >= vidkv_workspace_bytes(params, 2) bytes
+ * With Tq == 0 this is plain attention over the residual tokens; a sequence
+ * with no token at all gets zeros.                                            */
+vidkv_status vidkv_decode_attention(const vidkv_params *params, int32_t layer,
+                                    const void *q_dev, const void *packed_K_dev,
+                                    const void *packed_V_dev, const void *K_tail_dev,
+                                    const void *V_tail_dev, int32_t tail_capacity,
+                                    const int32_t *tail_len_dev, void *out_dev,
+                                    void *workspace_dev, size_t workspace_bytes,
+                                    void *hip_stream);
+
+/* Measurement aid, not part of the method: dst[i] = src[i] for `bytes` bytes
+ * (multiple of 16, both 16-byte aligned) with the library's streaming access
+ * pattern; used to calibrate hardware byte counters and the achievable HBM
+ * rate. */
+vidkv_status vidkv_calib_copy(void *dst_dev, const void *src_dev, size_t bytes,
+                              void *hip_stream);
+
+const char *vidkv_status_string(vidkv_status status);
+int vidkv_abi_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* VIDKV_H */

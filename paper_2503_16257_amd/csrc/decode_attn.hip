@@ -1,0 +1,297 @@
+// Decode attention over the packed cache (Eq. 3; Alg. 1, Decoding):
+// split-T partial softmax-attention with the dequantization fused in, then a
+// log-sum-exp merge.  The dequantized K', V' never exist in memory.
+//
+// Normal key channels are scored in the frequency domain: by linearity
+//   sum_c q_c IDFT(Xhat_c)[t] = IDFT(sum_c q_c Xhat_c)[t],
+// so per 32-token group the +-s coefficients are contracted over channels first
+// (Y[h][slot]) and a single 32-point inverse real DFT per query head follows.
+#include "vidkv_common.h"
+
+namespace vidkv {
+
+struct AttnArgs {
+  const _Float16* q;         // [B, Hq, 128]
+  const uint8_t* kperm;      // key PERM section (whole buffer)
+  const uint8_t* krec;       // key REC section (whole buffer)
+  const uint8_t* vrec;       // value REC section (whole buffer)
+  const uint32_t* vmask;     // [B, ng] or unused
+  const uint32_t* vrank;     // [B, ng]
+  const _Float16* vrows;     // [L, B, H, n_s, 128]
+  const _Float16* ktail;     // [B, H, cap, 128]
+  const _Float16* vtail;
+  const int32_t* tail_len;   // [B] or NULL
+  float* part;               // [(nsplit+1), B, Hq, 130]
+  int layer, B, H, Hq, rep, ng, n_a, n_n, n_s, krec_bytes, cap, nsplit, gps;
+  float scale;
+};
+
+__device__ const float kCos[32] = {
+    cos32(0),  cos32(1),  cos32(2),  cos32(3),  cos32(4),  cos32(5),  cos32(6),  cos32(7),
+    cos32(8),  cos32(9),  cos32(10), cos32(11), cos32(12), cos32(13), cos32(14), cos32(15),
+    cos32(16), cos32(17), cos32(18), cos32(19), cos32(20), cos32(21), cos32(22), cos32(23),
+    cos32(24), cos32(25), cos32(26), cos32(27), cos32(28), cos32(29), cos32(30), cos32(31)};
+
+constexpr int PART_STRIDE = D + 2;   // o[128], m, l
+
+// One workgroup = one (split, KV head, sequence); 256 threads.  blockIdx.x ==
+// nsplit is the block that handles the fp16 residual tokens.
+__global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
+  const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
+  const int tid = threadIdx.x;
+  const int R = a.rep;
+  const long long hd = ((long long)a.layer * a.B + b) * a.H + kvh;
+
+  __shared__ float qp[MAX_REP][D];          // q in PERM order (anomalous first)
+  __shared__ float qu[MAX_REP][D];          // q in channel order
+  __shared__ u32x4 krec4[1536 / 16];
+  __shared__ u32x4 vrec4[VREC / 16];
+  __shared__ float Y[MAX_REP][32];
+  __shared__ float P[MAX_REP][32];
+  __shared__ float Alpha[MAX_REP];
+  __shared__ float cs[32], sn[32];
+
+  if (tid < 32) { cs[tid] = kCos[tid]; sn[tid] = kCos[(tid + 24) & 31]; }   // sin x = cos(x - pi/2)
+  for (int i = tid; i < R * D; i += 256) {
+    const int h = i >> 7, c = i & 127;
+    const _Float16* qrow = a.q + ((long long)b * a.Hq + kvh * R + h) * D;
+    qu[h][c] = (float)qrow[c];
+    qp[h][c] = (float)qrow[a.kperm[hd * D + c]];
+  }
+  __syncthreads();
+
+  // roles
+  const int t_s = tid & 31, h_s = tid >> 5;          // score / softmax role: (token, head)
+  const int c_o = tid & 127, half_o = tid >> 7;      // output role: channel, heads half_o + 2 i
+  float m_run = -INFINITY, l_run = 0.0f;             // valid in threads with h_s < R
+  float acc[4] = {0.f, 0.f, 0.f, 0.f};
+
+  const bool is_tail = (split == a.nsplit);
+  int n_iter, g_begin = 0, tl = 0;
+  if (!is_tail) {
+    g_begin = split * a.gps;
+    const int g_end = min(a.ng, g_begin + a.gps);
+    n_iter = max(0, g_end - g_begin);
+  } else {
+    tl = a.tail_len ? a.tail_len[b] : 0;
+    tl = min(max(tl, 0), a.cap);
+    n_iter = (tl + 31) / 32;
+  }
+
+  const uint16_t* kbits = reinterpret_cast<const uint16_t*>(krec4) + 6 * a.n_a;
+  const _Float16* krec16 = reinterpret_cast<const _Float16*>(krec4);
+  const uint8_t* kcodes = reinterpret_cast<const uint8_t*>(krec4);
+  const uint16_t* vwords = reinterpret_cast<const uint16_t*>(vrec4);
+  const _Float16* vscale = reinterpret_cast<const _Float16*>(vrec4) + 512;
+
+  for (int it = 0; it < n_iter; ++it) {
+    float score = -INFINITY;
+    uint32_t smask = 0, srank = 0;
+    const int g = g_begin + it;
+    if (!is_tail) {
+      // ---- stage the two records
+      const u32x4* ks = reinterpret_cast<const u32x4*>(a.krec + (hd * a.ng + g) * (long long)a.krec_bytes);
+      const u32x4* vs = reinterpret_cast<const u32x4*>(a.vrec + (hd * a.ng + g) * (long long)VREC);
+      if (tid < a.krec_bytes / 16) krec4[tid] = ks[tid];
+      if (tid >= 128 && tid - 128 < VREC / 16) vrec4[tid - 128] = vs[tid - 128];
+      if (a.n_s > 0) {
+        smask = a.vmask[(size_t)b * a.ng + g];
+        srank = a.vrank[(size_t)b * a.ng + g];
+      }
+      __syncthreads();
+      // ---- Y[h][slot] = sum over normal channels of q * (+-s)
+      if (h_s < R) {
+        const int slot = t_s, k = slot & 15, hi = slot >> 4;
+        const int use_im = (hi && k) ? 1 : 0;
+        float y = 0.0f;
+        for (int i = 0; i < a.n_n; ++i) {
+          const int blk = i >> 3, e = i & 7;
+          const uint32_t w = kbits[blk * 16 + k];
+          const float sgn = ((w >> (8 * hi + e)) & 1u) ? 1.0f : -1.0f;
+          const float s = (float)krec16[6 * a.n_a + 2 * a.n_n + (blk * 2 + use_im) * 8 + e];
+          y += qp[h_s][a.n_a + i] * (s * sgn);
+        }
+        Y[h_s][slot] = y;
+      }
+      __syncthreads();
+      // ---- score[h][t]: inverse real DFT of Y plus the 2-bit channels
+      if (h_s < R) {
+        const int t = t_s;
+        float v = Y[h_s][0] + ((t & 1) ? -Y[h_s][16] : Y[h_s][16]);
+        float w2 = 0.0f;
+#pragma unroll
+        for (int k = 1; k < 16; ++k) {
+          const int ph = (k * t) & 31;
+          w2 += Y[h_s][k] * cs[ph] - Y[h_s][16 + k] * sn[ph];
+        }
+        v = (v + 2.0f * w2) * (1.0f / 32.0f);
+        const int nq = a.n_a >> 2;
+        for (int j = 0; j < a.n_a; ++j) {
+          const uint32_t code = (kcodes[t * nq + (j >> 2)] >> (2 * (j & 3))) & 3u;
+          const float s = (float)krec16[4 * a.n_a + j], z = (float)krec16[5 * a.n_a + j];
+          v += qp[h_s][j] * ((float)code * s + z);
+        }
+        score = v * a.scale;
+      }
+    } else {
+      // ---- residual tokens: plain fp16 rows
+      const int tok = it * 32 + t_s;
+      if (h_s < R && tok < tl) {
+        const u32x4* row = reinterpret_cast<const u32x4*>(
+            a.ktail + (((long long)b * a.H + kvh) * a.cap + tok) * D);
+        float v = 0.0f;
+        for (int i = 0; i < 16; ++i) {
+          U4H u;
+          u.u = row[i];
+#pragma unroll
+          for (int e = 0; e < 8; ++e) v += qu[h_s][i * 8 + e] * (float)u.e[e];
+        }
+        score = v * a.scale;
+      }
+    }
+    // ---- online softmax over the 32 tokens of this step, per head
+    if (h_s < R) {
+      float mx = score;
+#pragma unroll
+      for (int d = 16; d >= 1; d >>= 1) mx = fmaxf(mx, __shfl_xor(mx, d, 32));
+      const float m_new = fmaxf(m_run, mx);
+      const float p = (score == -INFINITY) ? 0.0f : __expf(score - m_new);
+      const float al = (m_run == -INFINITY) ? 0.0f : __expf(m_run - m_new);
+      float ps = p;
+#pragma unroll
+      for (int d = 16; d >= 1; d >>= 1) ps += __shfl_xor(ps, d, 32);
+      l_run = l_run * al + ps;
+      m_run = m_new;
+      P[h_s][t_s] = p;
+      if (t_s == 0) Alpha[h_s] = al;
+    }
+    __syncthreads();
+    // ---- output accumulation
+    if (!is_tail) {
+      uint32_t w[4];
+#pragma unroll
+      for (int kb = 0; kb < 4; ++kb) w[kb] = vwords[(kb * 16 + (c_o & 15)) * 8 + (c_o >> 4)];
+      const float s = (float)vscale[c_o];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int h = half_o + 2 * i;
+        if (h < R) {
+          float dot = 0.0f;
+#pragma unroll
+          for (int t = 0; t < 32; ++t) {
+            const int kb = (t & 15) >> 2, j = (t & 3) + ((t >= 16) ? 4 : 0);
+            const uint32_t f = (w[kb] >> (8 * (j & 1) + 2 * (j >> 1))) & 3u;
+            const float val = (f & 1u) ? ((f & 2u) ? -1.0f : 1.0f) : 0.0f;
+            dot += P[h][t] * val;
+          }
+          acc[i] = acc[i] * Alpha[h] + s * dot;
+        }
+      }
+      uint32_t sm = smask;
+      uint32_t r = srank;
+      while (sm) {
+        const int t = __ffs(sm) - 1;
+        sm &= sm - 1;
+        const float v = (float)a.vrows[(hd * a.n_s + r) * D + c_o];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int h = half_o + 2 * i;
+          if (h < R) acc[i] += P[h][t] * v;
+        }
+        ++r;
+      }
+    } else {
+      const int nt = min(32, tl - it * 32);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int h = half_o + 2 * i;
+        if (h < R) acc[i] *= Alpha[h];
+      }
+      for (int t = 0; t < nt; ++t) {
+        const float v = (float)a.vtail[(((long long)b * a.H + kvh) * a.cap + it * 32 + t) * D + c_o];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int h = half_o + 2 * i;
+          if (h < R) acc[i] += P[h][t] * v;
+        }
+      }
+    }
+    __syncthreads();
+  }
+
+  // ---- write the partial (o, m, l) of every head of this KV head
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int h = half_o + 2 * i;
+    if (h < R) {
+      float* o = a.part + (((long long)split * a.B + b) * a.Hq + kvh * R + h) * PART_STRIDE;
+      o[c_o] = acc[i];
+    }
+  }
+  if (h_s < R && t_s == 0) {
+    float* o = a.part + (((long long)split * a.B + b) * a.Hq + kvh * R + h_s) * PART_STRIDE;
+    o[D] = m_run;
+    o[D + 1] = l_run;
+  }
+}
+
+// Merge of the split partials: out = sum_i o_i e^{m_i - M} / sum_i l_i e^{m_i - M}.
+// grid (Hq, B), block 128.
+__global__ __launch_bounds__(128) void attn_merge_kernel(const float* __restrict__ part, int nparts,
+                                                         int B, int Hq, _Float16* __restrict__ out) {
+  const int h = blockIdx.x, b = blockIdx.y, c = threadIdx.x;
+  float M = -INFINITY;
+  for (int i = 0; i < nparts; ++i)
+    M = fmaxf(M, part[(((long long)i * B + b) * Hq + h) * PART_STRIDE + D]);
+  float o = 0.0f, l = 0.0f;
+  if (M != -INFINITY) {
+    for (int i = 0; i < nparts; ++i) {
+      const float* p = part + (((long long)i * B + b) * Hq + h) * PART_STRIDE;
+      const float mi = p[D];
+      if (mi == -INFINITY) continue;
+      const float w = __expf(mi - M);
+      o += w * p[c];
+      l += w * p[D + 1];
+    }
+  }
+  out[((long long)b * Hq + h) * D + c] = (_Float16)(l > 0.0f ? o / l : 0.0f);
+}
+
+int attn_num_splits(const Geom& g) {
+  if (g.ng == 0) return 0;
+  const long long bh = (long long)g.B * g.H;
+  long long n = (1024 + bh - 1) / bh;
+  if (n < 1) n = 1;
+  if (n > g.ng) n = g.ng;
+  return (int)n;
+}
+
+hipError_t launch_decode_attention(const Geom& g, int layer, float scale, const void* q,
+                                   const uint8_t* pk, const uint8_t* pv, const void* ktail,
+                                   const void* vtail, int cap, const int32_t* tail_len, void* out,
+                                   void* ws, hipStream_t st) {
+  AttnArgs a;
+  a.q = reinterpret_cast<const _Float16*>(q);
+  a.kperm = pk + g.k_perm;
+  a.krec = pk + g.k_rec;
+  a.vrec = pv + g.v_rec;
+  a.vmask = reinterpret_cast<const uint32_t*>(pv + g.v_mask);
+  a.vrank = reinterpret_cast<const uint32_t*>(pv + g.v_rank);
+  a.vrows = reinterpret_cast<const _Float16*>(pv + g.v_rows);
+  a.ktail = reinterpret_cast<const _Float16*>(ktail);
+  a.vtail = reinterpret_cast<const _Float16*>(vtail);
+  a.tail_len = (cap > 0 && ktail && vtail) ? tail_len : nullptr;
+  a.part = reinterpret_cast<float*>(ws);
+  a.layer = layer; a.B = g.B; a.H = g.H; a.Hq = g.Hq; a.rep = g.rep; a.ng = g.ng;
+  a.n_a = g.n_a; a.n_n = g.n_n; a.n_s = g.n_s; a.krec_bytes = g.krec; a.cap = cap;
+  a.nsplit = attn_num_splits(g);
+  a.gps = a.nsplit ? (g.ng + a.nsplit - 1) / a.nsplit : 0;
+  a.scale = scale;
+  dim3 gr(a.nsplit + 1, g.H, g.B);
+  hipLaunchKernelGGL(attn_partial_kernel, gr, dim3(256), 0, st, a);
+  hipLaunchKernelGGL(attn_merge_kernel, dim3(g.Hq, g.B), dim3(128), 0, st, a.part, a.nsplit + 1,
+                     g.B, g.Hq, reinterpret_cast<_Float16*>(out));
+  return hipGetLastError();
+}
+
+}  // namespace vidkv

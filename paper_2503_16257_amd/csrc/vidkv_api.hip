@@ -1,0 +1,144 @@
+// C ABI of the VidKV library: argument validation on the host, then kernel
+// launches on the caller's stream.  Nothing here allocates or synchronizes.
+#include "vidkv_common.h"
+
+namespace vidkv {
+hipError_t launch_quantize_keys(const Geom& g, const void* K, uint8_t* packed, void* ws,
+                                hipStream_t st);
+hipError_t launch_quantize_values(const Geom& g, float gamma, const void* V, const float* scores,
+                                  const int32_t* idx, uint8_t* packed, hipStream_t st);
+hipError_t launch_decode_attention(const Geom& g, int layer, float scale, const void* q,
+                                   const uint8_t* pk, const uint8_t* pv, const void* ktail,
+                                   const void* vtail, int cap, const int32_t* tail_len, void* out,
+                                   void* ws, hipStream_t st);
+int attn_num_splits(const Geom& g);
+
+static size_t ws_keys(const Geom& g) {
+  return align256((size_t)g.nheads * g.range_chunks * 2 * D * sizeof(_Float16)) + 256;
+}
+static size_t ws_values(const Geom&) { return 256; }
+static size_t ws_attn(const Geom& g) {
+  return align256((size_t)(attn_num_splits(g) + 1) * g.B * g.Hq * (D + 2) * sizeof(float)) + 256;
+}
+static bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+__global__ __launch_bounds__(256) void calib_copy_kernel(const u32x4* __restrict__ src,
+                                                         u32x4* __restrict__ dst, size_t n) {
+  size_t i = (size_t)blockIdx.x * 1024 + threadIdx.x;
+#pragma unroll
+  for (int k = 0; k < 4; ++k, i += 256)
+    if (i < n) __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
+}
+}  // namespace vidkv
+
+using namespace vidkv;
+
+extern "C" {
+
+size_t vidkv_packed_keys_bytes(const vidkv_params* p) {
+  Geom g;
+  return make_geom(p, &g) ? g.k_total : 0;
+}
+
+size_t vidkv_packed_values_bytes(const vidkv_params* p) {
+  Geom g;
+  return make_geom(p, &g) ? g.v_total : 0;
+}
+
+size_t vidkv_workspace_bytes(const vidkv_params* p, int which) {
+  Geom g;
+  if (!make_geom(p, &g)) return 0;
+  switch (which) {
+    case 0: return ws_keys(g);
+    case 1: return ws_values(g);
+    case 2: return ws_attn(g);
+    default: return 0;
+  }
+}
+
+vidkv_status vidkv_quantize_keys(const vidkv_params* p, const void* K, void* packed,
+                                 size_t packed_bytes, void* ws, size_t ws_bytes, void* stream) {
+  Geom g;
+  if (!p || !packed || !ws) return VIDKV_EINVAL;
+  if (!make_geom(p, &g)) return VIDKV_ESHAPE;
+  if (g.T > 0 && !K) return VIDKV_EINVAL;
+  if (g.nheads > 65535) return VIDKV_ESHAPE;
+  if (!aligned(K, 16) || !aligned(packed, 256) || !aligned(ws, 256)) return VIDKV_EINVAL;
+  if (packed_bytes < g.k_total || ws_bytes < ws_keys(g)) return VIDKV_ENOSPACE;
+  const hipError_t e = launch_quantize_keys(g, K, static_cast<uint8_t*>(packed), ws,
+                                            static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? VIDKV_OK : VIDKV_EHIP;
+}
+
+vidkv_status vidkv_quantize_values(const vidkv_params* p, const void* V, const float* saliency,
+                                   const int32_t* salient_idx, void* packed, size_t packed_bytes,
+                                   void* ws, size_t ws_bytes, void* stream) {
+  Geom g;
+  if (!p || !packed || !ws) return VIDKV_EINVAL;
+  if (!make_geom(p, &g)) return VIDKV_ESHAPE;
+  if (g.T > 0 && !V) return VIDKV_EINVAL;
+  if (g.nheads > 65535) return VIDKV_ESHAPE;
+  if (g.n_s > 0 && ((saliency != nullptr) == (salient_idx != nullptr))) return VIDKV_EINVAL;
+  if (!(p->gamma >= 0.0f) || !(p->gamma < 1e30f)) return VIDKV_EINVAL;
+  if (!aligned(V, 16) || !aligned(packed, 256) || !aligned(saliency, 4) || !aligned(salient_idx, 4))
+    return VIDKV_EINVAL;
+  if (packed_bytes < g.v_total || ws_bytes < ws_values(g)) return VIDKV_ENOSPACE;
+  const hipError_t e =
+      launch_quantize_values(g, p->gamma, V, g.n_s > 0 ? saliency : nullptr,
+                             g.n_s > 0 ? salient_idx : nullptr, static_cast<uint8_t*>(packed),
+                             static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? VIDKV_OK : VIDKV_EHIP;
+}
+
+vidkv_status vidkv_decode_attention(const vidkv_params* p, int32_t layer, const void* q,
+                                    const void* packed_K, const void* packed_V, const void* K_tail,
+                                    const void* V_tail, int32_t tail_capacity,
+                                    const int32_t* tail_len, void* out, void* ws, size_t ws_bytes,
+                                    void* stream) {
+  Geom g;
+  if (!p || !q || !out || !ws) return VIDKV_EINVAL;
+  if (!make_geom(p, &g)) return VIDKV_ESHAPE;
+  if (layer < 0 || layer >= g.L) return VIDKV_EINVAL;
+  if (g.T > 0 && (!packed_K || !packed_V)) return VIDKV_EINVAL;
+  if (tail_capacity < 0) return VIDKV_EINVAL;
+  if (tail_capacity > 0 && tail_len && (!K_tail || !V_tail)) return VIDKV_EINVAL;
+  if (g.B > 65535 || g.H > 65535) return VIDKV_ESHAPE;
+  if (!(p->softmax_scale > 0.0f) || !(p->softmax_scale < 1e30f)) return VIDKV_EINVAL;
+  if (!aligned(q, 16) || !aligned(out, 16) || !aligned(packed_K, 256) || !aligned(packed_V, 256) ||
+      !aligned(K_tail, 16) || !aligned(V_tail, 16) || !aligned(ws, 256) || !aligned(tail_len, 4))
+    return VIDKV_EINVAL;
+  if (ws_bytes < ws_attn(g)) return VIDKV_ENOSPACE;
+  const hipError_t e = launch_decode_attention(
+      g, layer, p->softmax_scale, q, static_cast<const uint8_t*>(packed_K),
+      static_cast<const uint8_t*>(packed_V), K_tail, V_tail, tail_capacity, tail_len, out, ws,
+      static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? VIDKV_OK : VIDKV_EHIP;
+}
+
+vidkv_status vidkv_calib_copy(void* dst, const void* src, size_t bytes, void* stream) {
+  if (!dst || !src) return VIDKV_EINVAL;
+  if (bytes % 16 || !aligned(dst, 16) || !aligned(src, 16)) return VIDKV_EINVAL;
+  if (bytes == 0) return VIDKV_OK;
+  const size_t n = bytes / 16;
+  const size_t blocks = (n + 1023) / 1024;
+  if (blocks > 0x7fffffffull) return VIDKV_ESHAPE;
+  hipLaunchKernelGGL(calib_copy_kernel, dim3((unsigned)blocks), dim3(256), 0,
+                     static_cast<hipStream_t>(stream), static_cast<const u32x4*>(src),
+                     static_cast<u32x4*>(dst), n);
+  return hipGetLastError() == hipSuccess ? VIDKV_OK : VIDKV_EHIP;
+}
+
+const char* vidkv_status_string(vidkv_status s) {
+  switch (s) {
+    case VIDKV_OK: return "ok";
+    case VIDKV_EINVAL: return "invalid argument";
+    case VIDKV_ESHAPE: return "unsupported shape";
+    case VIDKV_ENOSPACE: return "buffer too small";
+    case VIDKV_EHIP: return "HIP runtime error";
+    default: return "unknown status";
+  }
+}
+
+int vidkv_abi_version(void) { return VIDKV_ABI_VERSION; }
+
+}  // extern "C"

@@ -1,0 +1,115 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every symbol the
+header declares, its size functions agree with the oracle's independent
+reading of the format, and every bad argument is refused before any launch."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from oracle import layout as LY
+from paper_2503_16257_amd import binding as vk
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    src = open(os.path.join(ROOT, "include", "vidkv.h")).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(vidkv_[a-z_0-9]+)\s*\(", src)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = _declared_functions()
+    assert {"vidkv_quantize_keys", "vidkv_quantize_values", "vidkv_decode_attention",
+            "vidkv_packed_keys_bytes", "vidkv_packed_values_bytes", "vidkv_workspace_bytes",
+            "vidkv_status_string", "vidkv_abi_version", "vidkv_calib_copy"} <= set(names)
+    L = C.CDLL(vk.LIB_PATH)
+    for n in names:
+        assert hasattr(L, n), n
+    assert vk.abi_version() == 1
+    assert vk.status_string(0) == "ok" and vk.status_string(3) == "buffer too small"
+
+
+@pytest.mark.parametrize("L_,B,H,Hq,T,n_a,n_s", [
+    (1, 1, 1, 1, 1568, 64, 156), (1, 1, 4, 28, 6272, 64, 0), (28, 8, 4, 28, 12544, 64, 0),
+    (1, 1, 4, 28, 196000, 16, 9800), (1, 64, 4, 28, 25088, 8, 5017), (2, 3, 2, 4, 64, 0, 1),
+    (1, 1, 1, 1, 0, 16, 0), (1, 1, 1, 8, 32, 128, 32),
+])
+def test_size_functions_match_format(L_, B, H, Hq, T, n_a, n_s):
+    p = vk.make_params(L_, B, H, Hq, T, n_a, n_s)
+    assert vk.packed_keys_bytes(p) == LY.key_sections(L_, B, H, T, n_a)["total"]
+    assert vk.packed_values_bytes(p) == LY.value_sections(L_, B, H, T, n_s)["total"]
+    for which in (0, 1, 2):
+        assert vk.workspace_bytes(p, which) >= 256
+    assert vk.workspace_bytes(p, 3) == 0
+
+
+def test_stored_bits_per_element():
+    """Stored key bytes per element = (12 n_a + 8 n_n)/4096; value record 1280/4096."""
+    for n_a, expect in ((8, 0.2578125), (16, 0.265625), (32, 0.28125), (64, 0.3125)):
+        assert LY.key_record_bytes(n_a) / 4096 == expect
+    assert LY.VREC / 4096 == 0.3125
+
+
+def test_invalid_params_give_zero_sizes():
+    bad = [
+        dict(n_anom=7), dict(n_anom=136), dict(t_quant=33), dict(t_quant=-32), dict(head_dim=64),
+        dict(group=64), dict(n_q_heads=5), dict(n_q_heads=36), dict(use_fft=0),
+        dict(n_salient=65), dict(n_salient=-1), dict(n_layers=0), dict(batch=0), dict(n_kv_heads=0),
+    ]
+    for kw in bad:
+        p = vk.make_params(1, 1, 4, 28, 64, 16, 0)
+        for k, v in kw.items():
+            setattr(p, k, v)
+        assert vk.packed_keys_bytes(p) == 0, kw
+        assert vk.packed_values_bytes(p) == 0, kw
+        assert vk.workspace_bytes(p, 0) == 0, kw
+    assert vk.lib().vidkv_packed_keys_bytes(None) == 0
+
+
+def test_entry_points_refuse_bad_arguments_before_launch():
+    """No GPU here: each call must return its status from the host-side checks.
+    The pointers are fake addresses that are never dereferenced."""
+    L = vk.lib()
+    p = vk.make_params(1, 1, 4, 28, 64, 16, 4)
+    pb = C.byref(p)
+    A = 0x10000            # 256-aligned fake device address
+    big = 1 << 30
+    kb, vb = vk.packed_keys_bytes(p), vk.packed_values_bytes(p)
+    # quantize_keys
+    assert L.vidkv_quantize_keys(None, A, A, big, A, big, None) == vk.EINVAL
+    assert L.vidkv_quantize_keys(pb, None, A, big, A, big, None) == vk.EINVAL
+    assert L.vidkv_quantize_keys(pb, A, None, big, A, big, None) == vk.EINVAL
+    assert L.vidkv_quantize_keys(pb, A, A, big, None, big, None) == vk.EINVAL
+    assert L.vidkv_quantize_keys(pb, A, A + 16, big, A, big, None) == vk.EINVAL     # misaligned
+    assert L.vidkv_quantize_keys(pb, A, A, kb - 1, A, big, None) == vk.ENOSPACE
+    assert L.vidkv_quantize_keys(pb, A, A, big, A, vk.workspace_bytes(p, 0) - 1, None) == vk.ENOSPACE
+    bad = vk.make_params(1, 1, 4, 28, 64, 12, 0)
+    assert L.vidkv_quantize_keys(C.byref(bad), A, A, big, A, big, None) == vk.ESHAPE
+    # quantize_values: exactly one of scores / indices
+    assert L.vidkv_quantize_values(pb, A, None, None, A, big, A, big, None) == vk.EINVAL
+    assert L.vidkv_quantize_values(pb, A, A, A, A, big, A, big, None) == vk.EINVAL
+    assert L.vidkv_quantize_values(pb, A, A, None, A, vb - 1, A, big, None) == vk.ENOSPACE
+    assert L.vidkv_quantize_values(pb, None, A, None, A, big, A, big, None) == vk.EINVAL
+    neg = vk.make_params(1, 1, 4, 28, 64, 16, 4, gamma=-0.5)
+    assert L.vidkv_quantize_values(C.byref(neg), A, A, None, A, big, A, big, None) == vk.EINVAL
+    # decode_attention
+    args = [pb, 0, A, A, A, None, None, 0, None, A, A, big, None]
+    def call(**kw):
+        a = list(args)
+        for k, v in kw.items():
+            a[int(k[1:])] = v
+        return L.vidkv_decode_attention(*a)
+    assert call(a1=1) == vk.EINVAL and call(a1=-1) == vk.EINVAL          # layer out of range
+    assert call(a2=None) == vk.EINVAL and call(a9=None) == vk.EINVAL
+    assert call(a3=None) == vk.EINVAL and call(a4=None) == vk.EINVAL
+    assert call(a7=-1) == vk.EINVAL
+    assert call(a7=8, a8=A) == vk.EINVAL                                  # tail_len without tails
+    assert call(a11=vk.workspace_bytes(p, 2) - 1) == vk.ENOSPACE
+    noscale = vk.make_params(1, 1, 4, 28, 64, 16, 4, softmax_scale=0.0)
+    assert call(a0=C.byref(noscale)) == vk.EINVAL
+    # calib copy
+    assert L.vidkv_calib_copy(None, A, 16, None) == vk.EINVAL
+    assert L.vidkv_calib_copy(A, A, 8, None) == vk.EINVAL
+    assert L.vidkv_calib_copy(A, A, 0, None) == vk.OK

@@ -1,0 +1,228 @@
+#!/usr/bin/env python3
+"""Benchmark of the VidKV hot path on one MI355X.
+
+One "step" = one pass of the whole path over one batch of synthetic input
+already resident in HBM: quantize keys (range pass, channel selection, coding
+pass), quantize values (protected-token selection from scores, ternary coding
+pass), then one decode-attention step per layer over the packed cache.
+
+Prints ONE JSON line.  `value` is visual tokens per second through the whole
+step; the per-kernel rooflines (algorithmic bytes / HIP-event time of that
+kernel alone) and the CPU oracle's rate on a bounded sample ride along.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+BYTES_V_PER_ELEM = 0.2625      # 1.6-bit trits + one fp16 scale per 32 elements
+
+
+def algorithmic_bytes(w):
+    """Bytes the method itself must move, per kernel, for workload w."""
+    N = w.L * w.B * w.Hkv * w.T * 128                       # elements per tensor
+    k_packed = (w.n_anom * 12 + (128 - w.n_anom) * 8) / 4096 * N
+    v_packed = BYTES_V_PER_ELEM * N
+    rows = 2.0 * N * (w.n_salient / max(w.T, 1))
+    tail = 2 * 2 * w.L * w.B * w.Hkv * w.T_tail * 128
+    qo = 2 * 2 * w.L * w.B * w.Hq * 128
+    return {
+        "k_range": 2.0 * N,
+        "k_encode": 2.0 * N + k_packed,
+        "v_encode": 2.0 * N + v_packed + rows + (4.0 * w.B * w.T if w.n_salient else 0.0),
+        "attn_partial": k_packed + v_packed + rows + tail + qo,
+        "fp16_input": 2 * 2.0 * N,
+    }
+
+
+def cpu_baseline(w, budget_tokens=196000):
+    """The oracle, as it stands, on a bounded sample: one KV head, first
+    `budget_tokens` tokens of the workload, all query heads of that KV head."""
+    import numpy as np
+    from oracle import vidkv_oracle as O
+    from paper_2503_16257_amd import synth
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    T = min(w.T, budget_tokens) // 32 * 32
+    K = synth.key_head(w, 0)[:T]
+    V = synth.value_head(w, 0)[:T]
+    n_s = (w.n_salient * T) // max(w.T, 1)
+    sc = synth.saliency(w)[0, :T]
+    rep = w.Hq // w.Hkv
+    q = synth.query(w, 0)[0, :rep]
+    t0 = time.perf_counter()
+    rec = O.quantize_keys_head(K, w.n_anom)
+    sal = O.select_salient_tokens(sc, n_s)
+    qv = O.ternary_quant(V, sal, float(np.float32(0.7)))
+    t1 = time.perf_counter()
+    Kd = O.dequantize_keys_head(rec)
+    Vd = O.ternary_dequant(qv["codes"], qv["s16"], sal, qv["rows"])
+    for h in range(rep):
+        O.attention_single_query(q[h], Kd, Vd, 1.0 / np.sqrt(128.0))
+    t2 = time.perf_counter()
+    # the sample is 1 of Hkv KV heads of one layer of one sequence
+    tok_equiv = T / w.Hkv
+    return {
+        "value": tok_equiv / (t2 - t0), "unit": "visual tokens/s", "cores": int(cores),
+        "kind": "oracle",
+        "sample": f"1 KV head x {T} tokens of {w.name} (quantize K+V, select, 1 decode step); "
+                  f"quantize {t1 - t0:.2f} s, attention {t2 - t1:.2f} s",
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="c4_long")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--kernel-iters", type=int, default=20)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
+              "use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2503_16257_amd import binding as vk
+    from paper_2503_16257_amd import synth
+
+    vk.lib()                                  # fail loudly if the library is not built
+    dev = "cuda:0"
+    w = synth.WORKLOADS[args.workload]
+    p = vk.make_params(w.L, w.B, w.Hkv, w.Hq, w.T, w.n_anom, w.n_salient,
+                       gamma=float(np.float32(0.7)))
+
+    # ---- inputs, resident in HBM.  NROT independent copies are rotated so that
+    # a step never finds its inputs in the 256 MB last-level cache.
+    N = w.n_heads * w.T * 128
+    in_bytes = 2 * N
+    NROT = max(2, min(6, int(1.2e9 // max(in_bytes, 1)) + 1)) if in_bytes < 1.2e9 else 1
+    K0 = torch.empty((w.L, w.B, w.Hkv, w.T, 128), dtype=torch.float16, device=dev)
+    V0 = torch.empty_like(K0)
+    for hd in range(w.n_heads):
+        K0.view(-1, w.T, 128)[hd].copy_(torch.from_numpy(synth.key_head(w, hd)))
+        V0.view(-1, w.T, 128)[hd].copy_(torch.from_numpy(synth.value_head(w, hd)))
+    Ks = [K0] + [K0.clone() for _ in range(NROT - 1)]
+    Vs = [V0] + [V0.clone() for _ in range(NROT - 1)]
+    sal = torch.from_numpy(synth.saliency(w)).to(dev) if w.n_salient else None
+    pkb, pvb = vk.packed_keys_bytes(p), vk.packed_values_bytes(p)
+    AROT = max(2, min(16, int(6e8 // max(pkb + pvb, 1)) + 1))
+    pks = [vk.alloc_bytes(pkb, dev) for _ in range(AROT)]
+    pvs = [vk.alloc_bytes(pvb, dev) for _ in range(AROT)]
+    ws = vk.alloc_bytes(max(vk.workspace_bytes(p, i) for i in range(3)), dev)
+    qs = [torch.from_numpy(synth.query(w, l)).to(dev) for l in range(w.L)]
+    out = torch.empty((w.B, w.Hq, 128), dtype=torch.float16, device=dev)
+    cap = max(w.T_tail, 0)
+    Kt = Vt = tl = None
+    if cap:
+        kt, vt = zip(*[synth.tail_heads(w, 0, b) for b in range(w.B)])
+        Kt = torch.from_numpy(np.stack(kt)).to(dev)
+        Vt = torch.from_numpy(np.stack(vt)).to(dev)
+        tl = torch.full((w.B,), cap, dtype=torch.int32, device=dev)
+
+    def q_keys(i, stages=None):
+        vk.quantize_keys(p, Ks[i % NROT], pks[i % AROT], ws, stages=stages)
+
+    def q_vals(i, stages=None):
+        vk.quantize_values(p, Vs[i % NROT], pvs[i % AROT], ws, saliency=sal, stages=stages)
+
+    def attn(i, stages=None):
+        for l in range(w.L):
+            vk.decode_attention(p, l, qs[l], pks[i % AROT], pvs[i % AROT], out, ws, K_tail=Kt,
+                                V_tail=Vt, tail_capacity=cap, tail_len=tl, stages=stages)
+
+    def step(i):
+        q_keys(i)
+        q_vals(i)
+        attn(i)
+
+    for i in range(AROT):                     # fill every rotated packed buffer once
+        step(i)
+    torch.cuda.synchronize()
+
+    def timed(fn, iters, warm=2):
+        for i in range(warm):
+            fn(i)
+        torch.cuda.synchronize()
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(iters):
+            fn(warm + i)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / iters * 1e-3          # seconds per call
+
+    # ---- the whole step: W warm-ups, exactly K timed steps
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i)
+    torch.cuda.synchronize()
+    t_step = (time.perf_counter() - t0) / args.steps
+
+    # ---- per-kernel times, each kernel alone between two events on its stream
+    ab = algorithmic_bytes(w)
+    it = args.kernel_iters
+    kt = {
+        "k_range": timed(lambda i: q_keys(i, 1), it),
+        "k_select": timed(lambda i: q_keys(i, 2), it),
+        "k_encode": timed(lambda i: q_keys(i, 4), it),
+        "v_select": timed(lambda i: q_vals(i, 1), it) if w.n_salient else 0.0,
+        "v_encode": timed(lambda i: q_vals(i, 2), it),
+        "attn_partial": timed(lambda i: attn(i, 1), it) / w.L,
+        "attn_merge": timed(lambda i: attn(i, 2), it) / w.L,
+    }
+    t_qk = timed(lambda i: q_keys(i), it)
+    t_qv = timed(lambda i: q_vals(i), it)
+    t_at = timed(lambda i: attn(i), it)
+
+    def roof(name, per_launch_div=1.0):
+        a = ab[name] / per_launch_div / kt[name] / 1e9
+        return {"kernel": name, "bound": "hbm", "achieved": round(a, 1), "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": round(a / HBM_PEAK_GBS, 4), "traffic": None,
+                "us": round(kt[name] * 1e6, 2)}
+
+    roofs = [roof("k_range"), roof("k_encode"), roof("v_encode"), roof("attn_partial", w.L)]
+    dominant = max(roofs, key=lambda r: r["us"] * (w.L if r["kernel"] == "attn_partial" else 1))
+    tokens = w.L * w.B * w.T
+    res = {
+        "metric": "visual tokens/s through quantize K + quantize V + 1 decode-attention step "
+                  "(packed KV); quantize GB/s and decode-attn tokens/s alongside",
+        "value": round(tokens / t_step, 1), "unit": "visual tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(t_step * 1e3, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16",
+        "data": "synthetic",
+        "config": {"workload": w.name, "layers": w.L, "batch": w.B, "kv_heads": w.Hkv,
+                   "q_heads": w.Hq, "t_quant": w.T, "t_tail": w.T_tail, "n_anom": w.n_anom,
+                   "n_salient": w.n_salient, "input_rotation": NROT, "cache_rotation": AROT},
+        "quantize_GBps_fp16_input": round(ab["fp16_input"] / (t_qk + t_qv) / 1e9, 1),
+        "quantize_ms": {"keys": round(t_qk * 1e3, 4), "values": round(t_qv * 1e3, 4)},
+        "decode_attn_visual_tokens_per_s": round(tokens / t_at, 1),
+        "decode_attn_ms": round(t_at * 1e3, 4),
+        "kernel_us": {k: round(v * 1e6, 2) for k, v in kt.items()},
+        "roofline": {k: v for k, v in dominant.items() if k != "us"},
+        "rooflines": roofs,
+    }
+    if not args.no_cpu:
+        res["cpu_baseline"] = cpu_baseline(w)
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

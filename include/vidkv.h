@@ -134,6 +134,34 @@ vidkv_status vidkv_decode_attention(const vidkv_params *params, int32_t layer,
                                     void *workspace_dev, size_t workspace_bytes,
                                     void *hip_stream);
 
+/* Measurement aids, not part of the method.  Each takes the arguments of the
+ * entry point it is named after, checks them the same way, and launches only
+ * the kernels selected by `stages`, so that a benchmark can bracket a single
+ * kernel with events.  The buffers must already hold what the skipped kernels
+ * would have written (run the full entry point once first).
+ *   quantize_keys   : bit 0 per-channel min/max over all tokens (Alg. 3, range)
+ *                     bit 1 top-n_anom channel selection
+ *                     bit 2 per-group coding pass (Eq. 4 and Eq. 5)
+ *   quantize_values : bit 0 protected-token selection, bit 1 ternary coding pass
+ *   decode_attention: bit 0 split-T partial attention, bit 1 merge              */
+vidkv_status vidkv_quantize_keys_stages(const vidkv_params *params, const void *K_dev,
+                                        void *packed_K_dev, size_t packed_bytes,
+                                        void *workspace_dev, size_t workspace_bytes,
+                                        uint32_t stages, void *hip_stream);
+vidkv_status vidkv_quantize_values_stages(const vidkv_params *params, const void *V_dev,
+                                          const float *saliency_dev,
+                                          const int32_t *salient_idx_dev, void *packed_V_dev,
+                                          size_t packed_bytes, void *workspace_dev,
+                                          size_t workspace_bytes, uint32_t stages,
+                                          void *hip_stream);
+vidkv_status vidkv_decode_attention_stages(const vidkv_params *params, int32_t layer,
+                                           const void *q_dev, const void *packed_K_dev,
+                                           const void *packed_V_dev, const void *K_tail_dev,
+                                           const void *V_tail_dev, int32_t tail_capacity,
+                                           const int32_t *tail_len_dev, void *out_dev,
+                                           void *workspace_dev, size_t workspace_bytes,
+                                           uint32_t stages, void *hip_stream);
+
 /* Measurement aid, not part of the method: dst[i] = src[i] for `bytes` bytes
  * (multiple of 16, both 16-byte aligned) with the library's streaming access
  * pattern; used to calibrate hardware byte counters and the achievable HBM

@@ -57,6 +57,14 @@ def lib() -> C.CDLL:
         L.vidkv_quantize_values.restype = C.c_int
         L.vidkv_decode_attention.argtypes = [PP, i32, vp, vp, vp, vp, vp, i32, vp, vp, vp, sz, vp]
         L.vidkv_decode_attention.restype = C.c_int
+        u32 = C.c_uint32
+        L.vidkv_quantize_keys_stages.argtypes = [PP, vp, vp, sz, vp, sz, u32, vp]
+        L.vidkv_quantize_keys_stages.restype = C.c_int
+        L.vidkv_quantize_values_stages.argtypes = [PP, vp, vp, vp, vp, sz, vp, sz, u32, vp]
+        L.vidkv_quantize_values_stages.restype = C.c_int
+        L.vidkv_decode_attention_stages.argtypes = [PP, i32, vp, vp, vp, vp, vp, i32, vp, vp, vp,
+                                                    sz, u32, vp]
+        L.vidkv_decode_attention_stages.restype = C.c_int
         L.vidkv_calib_copy.argtypes = [vp, vp, sz, vp]
         L.vidkv_calib_copy.restype = C.c_int
         L.vidkv_status_string.argtypes = [C.c_int]
@@ -124,37 +132,48 @@ def _check(status: int, where: str):
         raise VidkvError(status, where)
 
 
-def quantize_keys(p: VidkvParams, K, packed_K, workspace, stream=None) -> None:
-    """vidkv_quantize_keys: K [L,B,Hkv,Tq,128] fp16 -> packed_K (uint8 buffer)."""
+def quantize_keys(p: VidkvParams, K, packed_K, workspace, stream=None, stages=None) -> None:
+    """vidkv_quantize_keys: K [L,B,Hkv,Tq,128] fp16 -> packed_K (uint8 buffer).
+    With `stages` (bit mask) calls vidkv_quantize_keys_stages instead."""
     import torch
-    _check(lib().vidkv_quantize_keys(
-        C.byref(p), _ptr(K, torch.float16, "K"), _ptr(packed_K, torch.uint8, "packed_K"),
-        _nbytes(packed_K), _ptr(workspace, torch.uint8, "workspace"), _nbytes(workspace),
-        _stream(stream)), "vidkv_quantize_keys")
+    a = [C.byref(p), _ptr(K, torch.float16, "K"), _ptr(packed_K, torch.uint8, "packed_K"),
+         _nbytes(packed_K), _ptr(workspace, torch.uint8, "workspace"), _nbytes(workspace)]
+    if stages is None:
+        _check(lib().vidkv_quantize_keys(*a, _stream(stream)), "vidkv_quantize_keys")
+    else:
+        _check(lib().vidkv_quantize_keys_stages(*a, stages, _stream(stream)),
+               "vidkv_quantize_keys_stages")
 
 
 def quantize_values(p: VidkvParams, V, packed_V, workspace, saliency=None, salient_idx=None,
-                    stream=None) -> None:
+                    stream=None, stages=None) -> None:
     """vidkv_quantize_values: V fp16 (+ scores [B,Tq] f32 or indices [B,n_s] i32) -> packed_V."""
     import torch
-    _check(lib().vidkv_quantize_values(
-        C.byref(p), _ptr(V, torch.float16, "V"), _ptr(saliency, torch.float32, "saliency"),
-        _ptr(salient_idx, torch.int32, "salient_idx"), _ptr(packed_V, torch.uint8, "packed_V"),
-        _nbytes(packed_V), _ptr(workspace, torch.uint8, "workspace"), _nbytes(workspace),
-        _stream(stream)), "vidkv_quantize_values")
+    a = [C.byref(p), _ptr(V, torch.float16, "V"), _ptr(saliency, torch.float32, "saliency"),
+         _ptr(salient_idx, torch.int32, "salient_idx"), _ptr(packed_V, torch.uint8, "packed_V"),
+         _nbytes(packed_V), _ptr(workspace, torch.uint8, "workspace"), _nbytes(workspace)]
+    if stages is None:
+        _check(lib().vidkv_quantize_values(*a, _stream(stream)), "vidkv_quantize_values")
+    else:
+        _check(lib().vidkv_quantize_values_stages(*a, stages, _stream(stream)),
+               "vidkv_quantize_values_stages")
 
 
 def decode_attention(p: VidkvParams, layer: int, q, packed_K, packed_V, out, workspace,
                      K_tail=None, V_tail=None, tail_capacity: int = 0, tail_len=None,
-                     stream=None) -> None:
+                     stream=None, stages=None) -> None:
     """vidkv_decode_attention: one decode step of one layer -> out [B,Hq,128] fp16."""
     import torch
-    _check(lib().vidkv_decode_attention(
-        C.byref(p), layer, _ptr(q, torch.float16, "q"), _ptr(packed_K, torch.uint8, "packed_K"),
-        _ptr(packed_V, torch.uint8, "packed_V"), _ptr(K_tail, torch.float16, "K_tail"),
-        _ptr(V_tail, torch.float16, "V_tail"), tail_capacity, _ptr(tail_len, torch.int32, "tail_len"),
-        _ptr(out, torch.float16, "out"), _ptr(workspace, torch.uint8, "workspace"),
-        _nbytes(workspace), _stream(stream)), "vidkv_decode_attention")
+    a = [C.byref(p), layer, _ptr(q, torch.float16, "q"), _ptr(packed_K, torch.uint8, "packed_K"),
+         _ptr(packed_V, torch.uint8, "packed_V"), _ptr(K_tail, torch.float16, "K_tail"),
+         _ptr(V_tail, torch.float16, "V_tail"), tail_capacity, _ptr(tail_len, torch.int32, "tail_len"),
+         _ptr(out, torch.float16, "out"), _ptr(workspace, torch.uint8, "workspace"),
+         _nbytes(workspace)]
+    if stages is None:
+        _check(lib().vidkv_decode_attention(*a, _stream(stream)), "vidkv_decode_attention")
+    else:
+        _check(lib().vidkv_decode_attention_stages(*a, stages, _stream(stream)),
+               "vidkv_decode_attention_stages")
 
 
 def calib_copy(dst, src, stream=None) -> None:

@@ -269,7 +269,7 @@ int attn_num_splits(const Geom& g) {
 hipError_t launch_decode_attention(const Geom& g, int layer, float scale, const void* q,
                                    const uint8_t* pk, const uint8_t* pv, const void* ktail,
                                    const void* vtail, int cap, const int32_t* tail_len, void* out,
-                                   void* ws, hipStream_t st) {
+                                   void* ws, unsigned stages, hipStream_t st) {
   AttnArgs a;
   a.q = reinterpret_cast<const _Float16*>(q);
   a.kperm = pk + g.k_perm;
@@ -288,8 +288,10 @@ hipError_t launch_decode_attention(const Geom& g, int layer, float scale, const 
   a.gps = a.nsplit ? (g.ng + a.nsplit - 1) / a.nsplit : 0;
   a.scale = scale;
   dim3 gr(a.nsplit + 1, g.H, g.B);
-  hipLaunchKernelGGL(attn_partial_kernel, gr, dim3(256), 0, st, a);
-  hipLaunchKernelGGL(attn_merge_kernel, dim3(g.Hq, g.B), dim3(128), 0, st, a.part, a.nsplit + 1,
+  // stages: bit 0 split-T partial kernel, bit 1 merge
+  if (stages & 1u) hipLaunchKernelGGL(attn_partial_kernel, gr, dim3(256), 0, st, a);
+  if (stages & 2u)
+    hipLaunchKernelGGL(attn_merge_kernel, dim3(g.Hq, g.B), dim3(128), 0, st, a.part, a.nsplit + 1,
                      g.B, g.Hq, reinterpret_cast<_Float16*>(out));
   return hipGetLastError();
 }

@@ -248,18 +248,22 @@ __global__ __launch_bounds__(128) void k_encode_kernel(const u32x4* __restrict__
 }
 
 // ---------------------------------------------------------------------------
+// stages: bit 0 range pass, bit 1 channel selection, bit 2 coding pass
 hipError_t launch_quantize_keys(const Geom& g, const void* K, uint8_t* packed, void* ws,
-                                hipStream_t st) {
+                                unsigned stages, hipStream_t st) {
   if (g.T == 0) return hipSuccess;
   _Float16* w = reinterpret_cast<_Float16*>(ws);
   dim3 gr1(g.range_chunks, (unsigned)g.nheads);
-  hipLaunchKernelGGL(k_range_kernel, gr1, dim3(256), 0, st, reinterpret_cast<const u32x4*>(K),
-                     g.T, g.range_chunks, w);
-  hipLaunchKernelGGL(k_select_kernel, dim3((unsigned)g.nheads), dim3(128), 0, st, w,
-                     g.range_chunks, g.n_a, packed + g.k_perm);
+  if (stages & 1u)
+    hipLaunchKernelGGL(k_range_kernel, gr1, dim3(256), 0, st, reinterpret_cast<const u32x4*>(K),
+                       g.T, g.range_chunks, w);
+  if (stages & 2u)
+    hipLaunchKernelGGL(k_select_kernel, dim3((unsigned)g.nheads), dim3(128), 0, st, w,
+                       g.range_chunks, g.n_a, packed + g.k_perm);
   dim3 gr3(g.ng, (unsigned)g.nheads);
-  hipLaunchKernelGGL(k_encode_kernel, gr3, dim3(128), 0, st, reinterpret_cast<const u32x4*>(K),
-                     packed + g.k_perm, g.T, g.ng, g.n_a, g.krec, packed + g.k_rec);
+  if (stages & 4u)
+    hipLaunchKernelGGL(k_encode_kernel, gr3, dim3(128), 0, st, reinterpret_cast<const u32x4*>(K),
+                       packed + g.k_perm, g.T, g.ng, g.n_a, g.krec, packed + g.k_rec);
   return hipGetLastError();
 }
 

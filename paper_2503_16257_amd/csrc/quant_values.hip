@@ -195,18 +195,21 @@ __global__ __launch_bounds__(128) void v_encode_kernel(const u32x4* __restrict__
 }
 
 hipError_t launch_quantize_values(const Geom& g, float gamma, const void* V, const float* scores,
-                                  const int32_t* idx, uint8_t* packed, hipStream_t st) {
+                                  const int32_t* idx, uint8_t* packed, unsigned stages,
+                                  hipStream_t st) {
   if (g.T == 0) return hipSuccess;
   uint32_t* mask = reinterpret_cast<uint32_t*>(packed + g.v_mask);
   uint32_t* rank = reinterpret_cast<uint32_t*>(packed + g.v_rank);
-  if (g.n_s > 0) {
+  // stages: bit 0 protected-token selection, bit 1 coding pass
+  if (g.n_s > 0 && (stages & 1u)) {
     hipLaunchKernelGGL(v_select_kernel, dim3(g.B), dim3(1024), 0, st, scores, idx, g.T, g.ng,
                        g.n_s, reinterpret_cast<int32_t*>(packed + g.v_idx), mask, rank);
   }
   dim3 gr(g.ng, (unsigned)g.nheads);
-  hipLaunchKernelGGL(v_encode_kernel, gr, dim3(128), 0, st, reinterpret_cast<const u32x4*>(V),
-                     g.T, g.ng, g.B, g.H, g.n_s, gamma, mask, rank, packed + g.v_rec,
-                     reinterpret_cast<u32x4*>(packed + g.v_rows));
+  if (stages & 2u)
+    hipLaunchKernelGGL(v_encode_kernel, gr, dim3(128), 0, st, reinterpret_cast<const u32x4*>(V),
+                       g.T, g.ng, g.B, g.H, g.n_s, gamma, mask, rank, packed + g.v_rec,
+                       reinterpret_cast<u32x4*>(packed + g.v_rows));
   return hipGetLastError();
 }
 

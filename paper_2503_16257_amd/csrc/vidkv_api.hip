@@ -4,13 +4,14 @@
 
 namespace vidkv {
 hipError_t launch_quantize_keys(const Geom& g, const void* K, uint8_t* packed, void* ws,
-                                hipStream_t st);
+                                unsigned stages, hipStream_t st);
 hipError_t launch_quantize_values(const Geom& g, float gamma, const void* V, const float* scores,
-                                  const int32_t* idx, uint8_t* packed, hipStream_t st);
+                                  const int32_t* idx, uint8_t* packed, unsigned stages,
+                                  hipStream_t st);
 hipError_t launch_decode_attention(const Geom& g, int layer, float scale, const void* q,
                                    const uint8_t* pk, const uint8_t* pv, const void* ktail,
                                    const void* vtail, int cap, const int32_t* tail_len, void* out,
-                                   void* ws, hipStream_t st);
+                                   void* ws, unsigned stages, hipStream_t st);
 int attn_num_splits(const Geom& g);
 
 static size_t ws_keys(const Geom& g) {
@@ -56,8 +57,9 @@ size_t vidkv_workspace_bytes(const vidkv_params* p, int which) {
   }
 }
 
-vidkv_status vidkv_quantize_keys(const vidkv_params* p, const void* K, void* packed,
-                                 size_t packed_bytes, void* ws, size_t ws_bytes, void* stream) {
+vidkv_status vidkv_quantize_keys_stages(const vidkv_params* p, const void* K, void* packed,
+                                        size_t packed_bytes, void* ws, size_t ws_bytes,
+                                        uint32_t stages, void* stream) {
   Geom g;
   if (!p || !packed || !ws) return VIDKV_EINVAL;
   if (!make_geom(p, &g)) return VIDKV_ESHAPE;
@@ -65,14 +67,20 @@ vidkv_status vidkv_quantize_keys(const vidkv_params* p, const void* K, void* pac
   if (g.nheads > 65535) return VIDKV_ESHAPE;
   if (!aligned(K, 16) || !aligned(packed, 256) || !aligned(ws, 256)) return VIDKV_EINVAL;
   if (packed_bytes < g.k_total || ws_bytes < ws_keys(g)) return VIDKV_ENOSPACE;
-  const hipError_t e = launch_quantize_keys(g, K, static_cast<uint8_t*>(packed), ws,
+  const hipError_t e = launch_quantize_keys(g, K, static_cast<uint8_t*>(packed), ws, stages,
                                             static_cast<hipStream_t>(stream));
   return e == hipSuccess ? VIDKV_OK : VIDKV_EHIP;
 }
 
-vidkv_status vidkv_quantize_values(const vidkv_params* p, const void* V, const float* saliency,
-                                   const int32_t* salient_idx, void* packed, size_t packed_bytes,
-                                   void* ws, size_t ws_bytes, void* stream) {
+vidkv_status vidkv_quantize_keys(const vidkv_params* p, const void* K, void* packed,
+                                 size_t packed_bytes, void* ws, size_t ws_bytes, void* stream) {
+  return vidkv_quantize_keys_stages(p, K, packed, packed_bytes, ws, ws_bytes, ~0u, stream);
+}
+
+vidkv_status vidkv_quantize_values_stages(const vidkv_params* p, const void* V,
+                                          const float* saliency, const int32_t* salient_idx,
+                                          void* packed, size_t packed_bytes, void* ws,
+                                          size_t ws_bytes, uint32_t stages, void* stream) {
   Geom g;
   if (!p || !packed || !ws) return VIDKV_EINVAL;
   if (!make_geom(p, &g)) return VIDKV_ESHAPE;
@@ -86,15 +94,23 @@ vidkv_status vidkv_quantize_values(const vidkv_params* p, const void* V, const f
   const hipError_t e =
       launch_quantize_values(g, p->gamma, V, g.n_s > 0 ? saliency : nullptr,
                              g.n_s > 0 ? salient_idx : nullptr, static_cast<uint8_t*>(packed),
-                             static_cast<hipStream_t>(stream));
+                             stages, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? VIDKV_OK : VIDKV_EHIP;
 }
 
-vidkv_status vidkv_decode_attention(const vidkv_params* p, int32_t layer, const void* q,
-                                    const void* packed_K, const void* packed_V, const void* K_tail,
-                                    const void* V_tail, int32_t tail_capacity,
-                                    const int32_t* tail_len, void* out, void* ws, size_t ws_bytes,
-                                    void* stream) {
+vidkv_status vidkv_quantize_values(const vidkv_params* p, const void* V, const float* saliency,
+                                   const int32_t* salient_idx, void* packed, size_t packed_bytes,
+                                   void* ws, size_t ws_bytes, void* stream) {
+  return vidkv_quantize_values_stages(p, V, saliency, salient_idx, packed, packed_bytes, ws,
+                                      ws_bytes, ~0u, stream);
+}
+
+vidkv_status vidkv_decode_attention_stages(const vidkv_params* p, int32_t layer, const void* q,
+                                           const void* packed_K, const void* packed_V,
+                                           const void* K_tail, const void* V_tail,
+                                           int32_t tail_capacity, const int32_t* tail_len,
+                                           void* out, void* ws, size_t ws_bytes, uint32_t stages,
+                                           void* stream) {
   Geom g;
   if (!p || !q || !out || !ws) return VIDKV_EINVAL;
   if (!make_geom(p, &g)) return VIDKV_ESHAPE;
@@ -111,8 +127,17 @@ vidkv_status vidkv_decode_attention(const vidkv_params* p, int32_t layer, const 
   const hipError_t e = launch_decode_attention(
       g, layer, p->softmax_scale, q, static_cast<const uint8_t*>(packed_K),
       static_cast<const uint8_t*>(packed_V), K_tail, V_tail, tail_capacity, tail_len, out, ws,
-      static_cast<hipStream_t>(stream));
+      stages, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? VIDKV_OK : VIDKV_EHIP;
+}
+
+vidkv_status vidkv_decode_attention(const vidkv_params* p, int32_t layer, const void* q,
+                                    const void* packed_K, const void* packed_V, const void* K_tail,
+                                    const void* V_tail, int32_t tail_capacity,
+                                    const int32_t* tail_len, void* out, void* ws, size_t ws_bytes,
+                                    void* stream) {
+  return vidkv_decode_attention_stages(p, layer, q, packed_K, packed_V, K_tail, V_tail,
+                                       tail_capacity, tail_len, out, ws, ws_bytes, ~0u, stream);
 }
 
 vidkv_status vidkv_calib_copy(void* dst, const void* src, size_t bytes, void* stream) {

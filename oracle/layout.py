@@ -31,12 +31,14 @@ Key buffer
                            block's 8 channels.
 Value buffer
   section REC    : [LBH][T/32] records of 1280 bytes:
-      +0          trits  : uint16 [4][16][8]; word (kb, r, m) holds 8 tokens of
-                           channel c = 16*m + r: token slots j = 0..7 are
-                           tokens 4*kb + j (j < 4) and 16 + 4*kb + (j-4)
-                           (j >= 4).  Slot j sits at bit 8*(j & 1) + 2*(j >> 1):
-                           that bit = code != 0, the next = code < 0.
-      +1024       s      : fp16 [128]   (Eq. 6 mean |V|)
+      +0          trits  : uint32 [4 kb][16 r][4 mp]; word (kb, r, mp) holds 8
+                           token slots of the two channels c = 16*m + r,
+                           m = 2*mp + mh (mh = 0, 1).  Slot j = 0..7 is token
+                           4*kb + j (j < 4) or 16 + 4*kb + (j-4) (j >= 4) of the
+                           group.  The 2-bit field of (mh, j) starts at bit
+                           8*mh + 16*(j & 1) + 2*(j >> 1): that bit = code != 0,
+                           the next = code < 0.
+      +1024       s      : fp16 [16 r][8 m]: Eq. 6 mean |V| of channel 16*m + r
   section IDX    : int32  [B][n_s]   protected token indices, ascending
   section MASK   : uint32 [B][T/32]  bit (t % 32) of word t/32 = token t protected
   section RANK   : uint32 [B][T/32]  number of protected tokens before group g
@@ -166,36 +168,41 @@ def _trit_position(t: int) -> tuple[int, int]:
     return kb, j
 
 
+def _trit_bit(m: int, j: int) -> int:
+    """First bit of the 2-bit field of (tile m, slot j) inside its 32-bit word."""
+    return 8 * (m & 1) + 16 * (j & 1) + 2 * (j >> 1)
+
+
 def pack_value_head(codes: np.ndarray, s16: np.ndarray) -> np.ndarray:
     """codes [g, 128, 32] in {-1,0,1}, s16 [g, 128] -> record bytes [g, 1280]."""
     ng = codes.shape[0]
-    words = np.zeros((ng, 4, 16, 8), dtype=np.uint16)
+    words = np.zeros((ng, 4, 16, 4), dtype=np.uint32)
     cm = codes.reshape(ng, 8, 16, G)                              # [g, m, r, t], c = 16 m + r
     for t in range(G):
         kb, j = _trit_position(t)
-        sh = 8 * (j & 1) + 2 * (j >> 1)
-        nz = (cm[..., t] != 0).astype(np.uint16)
-        ng_ = (cm[..., t] < 0).astype(np.uint16)
-        field = (nz | (ng_ << 1)) << sh                           # [g, m, r]
-        words[:, kb, :, :] |= field.transpose(0, 2, 1)
+        for m in range(8):
+            nz = (cm[:, m, :, t] != 0).astype(np.uint32)
+            ng_ = (cm[:, m, :, t] < 0).astype(np.uint32)
+            words[:, kb, :, m >> 1] |= (nz | (ng_ << 1)) << _trit_bit(m, j)
     out = np.zeros((ng, VREC), dtype=np.uint8)
-    out[:, 0:1024] = words.astype("<u2").view(np.uint8).reshape(ng, -1)
-    out[:, 1024:1280] = s16.astype("<f2").view(np.uint8).reshape(ng, -1)
+    out[:, 0:1024] = words.astype("<u4").view(np.uint8).reshape(ng, -1)
+    st = s16.reshape(ng, 8, 16).transpose(0, 2, 1)                # [g, r, m]
+    out[:, 1024:1280] = np.ascontiguousarray(st).astype("<f2").view(np.uint8).reshape(ng, -1)
     return out
 
 
 def unpack_value_head(recs: np.ndarray):
     """Record bytes [g, 1280] -> (codes [g, 128, 32] int8, s16 [g, 128])."""
     ng = recs.shape[0]
-    words = np.ascontiguousarray(recs[:, 0:1024]).view("<u2").reshape(ng, 4, 16, 8)
+    words = np.ascontiguousarray(recs[:, 0:1024]).view("<u4").reshape(ng, 4, 16, 4)
     codes = np.zeros((ng, 8, 16, G), dtype=np.int8)
     for t in range(G):
         kb, j = _trit_position(t)
-        sh = 8 * (j & 1) + 2 * (j >> 1)
-        f = (words[:, kb, :, :] >> sh) & 3                        # [g, r, m]
-        val = np.where(f & 1, np.where(f & 2, -1, 1), 0).astype(np.int8)
-        codes[..., t] = val.transpose(0, 2, 1)
-    s16 = np.ascontiguousarray(recs[:, 1024:1280]).view("<f2").reshape(ng, D)
+        for m in range(8):
+            f = (words[:, kb, :, m >> 1] >> _trit_bit(m, j)) & 3  # [g, r]
+            codes[:, m, :, t] = np.where(f & 1, np.where(f & 2, -1, 1), 0).astype(np.int8)
+    st = np.ascontiguousarray(recs[:, 1024:1280]).view("<f2").reshape(ng, 16, 8)
+    s16 = np.ascontiguousarray(st.transpose(0, 2, 1)).reshape(ng, D)
     return codes.reshape(ng, D, G), s16
 
 

@@ -1,0 +1,39 @@
+// Shared declarations of the decode-attention kernels.
+#pragma once
+#include "vidkv_common.h"
+
+namespace vidkv {
+
+struct AttnArgs {
+  const _Float16* q;         // [B, Hq, 128]
+  const uint8_t* kperm;      // key PERM section (whole buffer)
+  const uint8_t* krec;       // key REC section (whole buffer)
+  const uint8_t* vrec;       // value REC section (whole buffer)
+  const uint32_t* vmask;     // [B, ng] or unused
+  const uint32_t* vrank;     // [B, ng]
+  const _Float16* vrows;     // [L, B, H, n_s, 128]
+  const _Float16* ktail;     // [B, H, cap, 128]
+  const _Float16* vtail;
+  const int32_t* tail_len;   // [B] or NULL
+  float* part;               // [(nsplit+1), B, Hq, 130]
+  int layer, B, H, Hq, rep, ng, n_a, n_n, n_s, krec_bytes, cap, nsplit, gps;
+  int split0;                // added to blockIdx.x (tail-only launches start at nsplit)
+  float scale2;              // softmax scale * log2(e): scores live in the exp2 domain
+};
+
+// One split partial per (split, sequence, query head): o[128], m, l with
+// p = 2^(score2 - m), l = sum p, o = sum p v.
+constexpr int PART_STRIDE = D + 2;
+
+// cos(2 pi j / 32), j = 0..31, rounded to fp32 (quarter-turn values exact).
+static __device__ const float kCosT[32] = {
+    cos32(0),  cos32(1),  cos32(2),  cos32(3),  cos32(4),  cos32(5),  cos32(6),  cos32(7),
+    cos32(8),  cos32(9),  cos32(10), cos32(11), cos32(12), cos32(13), cos32(14), cos32(15),
+    cos32(16), cos32(17), cos32(18), cos32(19), cos32(20), cos32(21), cos32(22), cos32(23),
+    cos32(24), cos32(25), cos32(26), cos32(27), cos32(28), cos32(29), cos32(30), cos32(31)};
+
+// true if the MFMA kernel has an instantiation for this anomalous-channel count
+bool attn_mfma_supported(int n_a);
+void launch_attn_mfma(const AttnArgs& a, dim3 grid, hipStream_t st);
+
+}  // namespace vidkv

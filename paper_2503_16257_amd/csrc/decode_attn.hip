@@ -6,38 +6,18 @@
 //   sum_c q_c IDFT(Xhat_c)[t] = IDFT(sum_c q_c Xhat_c)[t],
 // so per 32-token group the +-s coefficients are contracted over channels first
 // (Y[h][slot]) and a single 32-point inverse real DFT per query head follows.
-#include "vidkv_common.h"
+//
+// This file holds the plain-VALU kernel (any anomalous-channel count, and the
+// fp16 residual tokens), the merge kernel and the launcher; the MFMA kernel
+// that handles the common channel counts is in decode_attn_mfma.hip.
+#include "decode_attn.h"
 
 namespace vidkv {
 
-struct AttnArgs {
-  const _Float16* q;         // [B, Hq, 128]
-  const uint8_t* kperm;      // key PERM section (whole buffer)
-  const uint8_t* krec;       // key REC section (whole buffer)
-  const uint8_t* vrec;       // value REC section (whole buffer)
-  const uint32_t* vmask;     // [B, ng] or unused
-  const uint32_t* vrank;     // [B, ng]
-  const _Float16* vrows;     // [L, B, H, n_s, 128]
-  const _Float16* ktail;     // [B, H, cap, 128]
-  const _Float16* vtail;
-  const int32_t* tail_len;   // [B] or NULL
-  float* part;               // [(nsplit+1), B, Hq, 130]
-  int layer, B, H, Hq, rep, ng, n_a, n_n, n_s, krec_bytes, cap, nsplit, gps;
-  float scale;
-};
-
-__device__ const float kCos[32] = {
-    cos32(0),  cos32(1),  cos32(2),  cos32(3),  cos32(4),  cos32(5),  cos32(6),  cos32(7),
-    cos32(8),  cos32(9),  cos32(10), cos32(11), cos32(12), cos32(13), cos32(14), cos32(15),
-    cos32(16), cos32(17), cos32(18), cos32(19), cos32(20), cos32(21), cos32(22), cos32(23),
-    cos32(24), cos32(25), cos32(26), cos32(27), cos32(28), cos32(29), cos32(30), cos32(31)};
-
-constexpr int PART_STRIDE = D + 2;   // o[128], m, l
-
-// One workgroup = one (split, KV head, sequence); 256 threads.  blockIdx.x ==
+// One workgroup = one (split, KV head, sequence); 256 threads.  Split index
 // nsplit is the block that handles the fp16 residual tokens.
 __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
-  const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
+  const int split = blockIdx.x + a.split0, kvh = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x;
   const int R = a.rep;
   const long long hd = ((long long)a.layer * a.B + b) * a.H + kvh;
@@ -51,12 +31,12 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
   __shared__ float Alpha[MAX_REP];
   __shared__ float cs[32], sn[32];
 
-  if (tid < 32) { cs[tid] = kCos[tid]; sn[tid] = kCos[(tid + 24) & 31]; }   // sin x = cos(x - pi/2)
+  if (tid < 32) { cs[tid] = kCosT[tid]; sn[tid] = kCosT[(tid + 24) & 31]; }   // sin x = cos(x - pi/2)
   for (int i = tid; i < R * D; i += 256) {
     const int h = i >> 7, c = i & 127;
     const _Float16* qrow = a.q + ((long long)b * a.Hq + kvh * R + h) * D;
     qu[h][c] = (float)qrow[c];
-    qp[h][c] = (float)qrow[a.kperm[hd * D + c]];
+    qp[h][c] = a.ng > 0 ? (float)qrow[a.kperm[hd * D + c]] : 0.0f;
   }
   __syncthreads();
 
@@ -81,7 +61,7 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
   const uint16_t* kbits = reinterpret_cast<const uint16_t*>(krec4) + 6 * a.n_a;
   const _Float16* krec16 = reinterpret_cast<const _Float16*>(krec4);
   const uint8_t* kcodes = reinterpret_cast<const uint8_t*>(krec4);
-  const uint16_t* vwords = reinterpret_cast<const uint16_t*>(vrec4);
+  const uint32_t* vwords = reinterpret_cast<const uint32_t*>(vrec4);
   const _Float16* vscale = reinterpret_cast<const _Float16*>(vrec4) + 512;
 
   for (int it = 0; it < n_iter; ++it) {
@@ -131,7 +111,7 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
           const float s = (float)krec16[4 * a.n_a + j], z = (float)krec16[5 * a.n_a + j];
           v += qp[h_s][j] * ((float)code * s + z);
         }
-        score = v * a.scale;
+        score = v * a.scale2;
       }
     } else {
       // ---- residual tokens: plain fp16 rows
@@ -146,17 +126,17 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
 #pragma unroll
           for (int e = 0; e < 8; ++e) v += qu[h_s][i * 8 + e] * (float)u.e[e];
         }
-        score = v * a.scale;
+        score = v * a.scale2;
       }
     }
-    // ---- online softmax over the 32 tokens of this step, per head
+    // ---- online softmax over the 32 tokens of this step, per head (exp2 domain)
     if (h_s < R) {
       float mx = score;
 #pragma unroll
       for (int d = 16; d >= 1; d >>= 1) mx = fmaxf(mx, __shfl_xor(mx, d, 32));
       const float m_new = fmaxf(m_run, mx);
-      const float p = (score == -INFINITY) ? 0.0f : __expf(score - m_new);
-      const float al = (m_run == -INFINITY) ? 0.0f : __expf(m_run - m_new);
+      const float p = (score == -INFINITY) ? 0.0f : exp2f(score - m_new);
+      const float al = (m_run == -INFINITY) ? 0.0f : exp2f(m_run - m_new);
       float ps = p;
 #pragma unroll
       for (int d = 16; d >= 1; d >>= 1) ps += __shfl_xor(ps, d, 32);
@@ -170,8 +150,8 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
     if (!is_tail) {
       uint32_t w[4];
 #pragma unroll
-      for (int kb = 0; kb < 4; ++kb) w[kb] = vwords[(kb * 16 + (c_o & 15)) * 8 + (c_o >> 4)];
-      const float s = (float)vscale[c_o];
+      for (int kb = 0; kb < 4; ++kb) w[kb] = vwords[(kb * 16 + (c_o & 15)) * 4 + (c_o >> 5)];
+      const float s = (float)vscale[(c_o & 15) * 8 + (c_o >> 4)];
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const int h = half_o + 2 * i;
@@ -180,7 +160,7 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
 #pragma unroll
           for (int t = 0; t < 32; ++t) {
             const int kb = (t & 15) >> 2, j = (t & 3) + ((t >= 16) ? 4 : 0);
-            const uint32_t f = (w[kb] >> (8 * (j & 1) + 2 * (j >> 1))) & 3u;
+            const uint32_t f = (w[kb] >> (8 * ((c_o >> 4) & 1) + 16 * (j & 1) + 2 * (j >> 1))) & 3u;
             const float val = (f & 1u) ? ((f & 2u) ? -1.0f : 1.0f) : 0.0f;
             dot += P[h][t] * val;
           }
@@ -235,34 +215,56 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
   }
 }
 
-// Merge of the split partials: out = sum_i o_i e^{m_i - M} / sum_i l_i e^{m_i - M}.
-// grid (Hq, B), block 128.
-__global__ __launch_bounds__(128) void attn_merge_kernel(const float* __restrict__ part, int nparts,
-                                                         int B, int Hq, _Float16* __restrict__ out) {
-  const int h = blockIdx.x, b = blockIdx.y, c = threadIdx.x;
+// Merge of the split partials: out = sum_i o_i 2^{m_i - M} / sum_i l_i 2^{m_i - M}.
+// grid (Hq, B), block 1024 = 128 channels x 8 slices of the split list.
+__global__ __launch_bounds__(1024) void attn_merge_kernel(const float* __restrict__ part,
+                                                          int nparts, int B, int Hq,
+                                                          _Float16* __restrict__ out) {
+  const int h = blockIdx.x, b = blockIdx.y;
+  const int c = threadIdx.x & 127, sl = threadIdx.x >> 7;
+  __shared__ float sM[8];
+  __shared__ float so[8][D];
+  __shared__ float sl_[8];
   float M = -INFINITY;
-  for (int i = 0; i < nparts; ++i)
+  for (int i = sl; i < nparts; i += 8)
     M = fmaxf(M, part[(((long long)i * B + b) * Hq + h) * PART_STRIDE + D]);
+  if (c == 0) sM[sl] = M;
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < 8; ++i) M = fmaxf(M, sM[i]);
   float o = 0.0f, l = 0.0f;
   if (M != -INFINITY) {
-    for (int i = 0; i < nparts; ++i) {
+    for (int i = sl; i < nparts; i += 8) {
       const float* p = part + (((long long)i * B + b) * Hq + h) * PART_STRIDE;
       const float mi = p[D];
       if (mi == -INFINITY) continue;
-      const float w = __expf(mi - M);
+      const float w = exp2f(mi - M);
       o += w * p[c];
       l += w * p[D + 1];
     }
   }
-  out[((long long)b * Hq + h) * D + c] = (_Float16)(l > 0.0f ? o / l : 0.0f);
+  so[sl][c] = o;
+  if (c == 0) sl_[sl] = l;
+  __syncthreads();
+  if (sl == 0) {
+#pragma unroll
+    for (int i = 1; i < 8; ++i) { o += so[i][c]; l += sl_[i]; }
+    out[((long long)b * Hq + h) * D + c] = (_Float16)(l > 0.0f ? o / l : 0.0f);
+  }
 }
 
+// Number of split-T workgroups per (sequence, KV head).
 int attn_num_splits(const Geom& g) {
   if (g.ng == 0) return 0;
   const long long bh = (long long)g.B * g.H;
-  long long n = (1024 + bh - 1) / bh;
+  const bool mfma = attn_mfma_supported(g.n_a);
+  // MFMA kernel: 4 waves per workgroup, each wave walks pairs of groups; aim at
+  // 512 workgroups on the chip and at least 2 pairs per wave.
+  const long long target = mfma ? 512 : 1024;
+  long long n = (target + bh - 1) / bh;
+  const long long units = mfma ? ((g.ng + 1) / 2 + 7) / 8 : g.ng;
+  if (n > units) n = units;
   if (n < 1) n = 1;
-  if (n > g.ng) n = g.ng;
   return (int)n;
 }
 
@@ -280,19 +282,36 @@ hipError_t launch_decode_attention(const Geom& g, int layer, float scale, const 
   a.vrows = reinterpret_cast<const _Float16*>(pv + g.v_rows);
   a.ktail = reinterpret_cast<const _Float16*>(ktail);
   a.vtail = reinterpret_cast<const _Float16*>(vtail);
-  a.tail_len = (cap > 0 && ktail && vtail) ? tail_len : nullptr;
+  const bool has_tail = cap > 0 && ktail && vtail && tail_len;
+  a.tail_len = has_tail ? tail_len : nullptr;
   a.part = reinterpret_cast<float*>(ws);
   a.layer = layer; a.B = g.B; a.H = g.H; a.Hq = g.Hq; a.rep = g.rep; a.ng = g.ng;
   a.n_a = g.n_a; a.n_n = g.n_n; a.n_s = g.n_s; a.krec_bytes = g.krec; a.cap = cap;
   a.nsplit = attn_num_splits(g);
-  a.gps = a.nsplit ? (g.ng + a.nsplit - 1) / a.nsplit : 0;
-  a.scale = scale;
-  dim3 gr(a.nsplit + 1, g.H, g.B);
-  // stages: bit 0 split-T partial kernel, bit 1 merge
-  if (stages & 1u) hipLaunchKernelGGL(attn_partial_kernel, gr, dim3(256), 0, st, a);
+  a.scale2 = scale * 1.4426950408889634f;
+  a.split0 = 0;
+  // stages: bit 0 split-T partial kernel(s), bit 1 merge
+  const bool mfma = a.nsplit > 0 && attn_mfma_supported(g.n_a);
+  // with the MFMA kernel the residual-token block is a launch of its own and is
+  // skipped when there is no residual buffer
+  const int nparts = (mfma && !has_tail) ? a.nsplit : a.nsplit + 1;
+  if (stages & 1u) {
+    if (mfma) {
+      const int npairs = (g.ng + 1) / 2;
+      a.gps = (npairs + a.nsplit - 1) / a.nsplit;          // pairs per split
+      launch_attn_mfma(a, dim3(a.nsplit, g.H, g.B), st);
+      if (has_tail) {
+        a.split0 = a.nsplit;
+        hipLaunchKernelGGL(attn_partial_kernel, dim3(1, g.H, g.B), dim3(256), 0, st, a);
+      }
+    } else {
+      a.gps = a.nsplit ? (g.ng + a.nsplit - 1) / a.nsplit : 0;
+      hipLaunchKernelGGL(attn_partial_kernel, dim3(a.nsplit + 1, g.H, g.B), dim3(256), 0, st, a);
+    }
+  }
   if (stages & 2u)
-    hipLaunchKernelGGL(attn_merge_kernel, dim3(g.Hq, g.B), dim3(128), 0, st, a.part, a.nsplit + 1,
-                     g.B, g.Hq, reinterpret_cast<_Float16*>(out));
+    hipLaunchKernelGGL(attn_merge_kernel, dim3(g.Hq, g.B), dim3(1024), 0, st, a.part, nparts,
+                       g.B, g.Hq, reinterpret_cast<_Float16*>(out));
   return hipGetLastError();
 }
 

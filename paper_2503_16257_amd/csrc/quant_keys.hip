@@ -79,36 +79,55 @@ __global__ __launch_bounds__(256) void k_range_kernel(const u32x4* __restrict__ 
 // ---------------------------------------------------------------------------
 // Channel selection: R_c = float(max) - float(min); the n_a largest (ties to
 // the lower channel) are anomalous.  perm = anomalous ascending, then normal
-// ascending.  grid nheads, block 128.
+// ascending.  grid nheads, block 1024: 8 slices of the chunk list per channel.
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(128) void k_select_kernel(const _Float16* __restrict__ ws, int chunks,
-                                                       int n_a, uint8_t* __restrict__ perm) {
+__global__ __launch_bounds__(1024) void k_select_kernel(const _Float16* __restrict__ ws,
+                                                        int chunks, int n_a,
+                                                        uint8_t* __restrict__ perm) {
   const long long hd = blockIdx.x;
-  const int c = threadIdx.x;
+  const int c = threadIdx.x & 127, part = threadIdx.x >> 7;
   const _Float16* p = ws + hd * chunks * 2 * D;
   _Float16 lo = (_Float16)65504.0f, hi = (_Float16)-65504.0f;
-  for (int k = 0; k < chunks; ++k) {
+  for (int k = part; k < chunks; k += 8) {
     const _Float16 a = p[(k * 2) * D + c], b = p[(k * 2 + 1) * D + c];
     lo = a < lo ? a : lo;
     hi = b > hi ? b : hi;
   }
+  __shared__ _Float16 slo[8][D], shi[8][D];
   __shared__ float R[D];
   __shared__ int flag[D];
-  const float r = (float)hi - (float)lo;
-  R[c] = r;
+  slo[part][c] = lo;
+  shi[part][c] = hi;
   __syncthreads();
-  int rank = 0;
-  for (int j = 0; j < D; ++j) {
-    const float rj = R[j];
-    rank += (rj > r || (rj == r && j < c)) ? 1 : 0;
+  float r = 0.0f;
+  if (part == 0) {
+#pragma unroll
+    for (int i = 1; i < 8; ++i) {
+      const _Float16 a = slo[i][c], b = shi[i][c];
+      lo = a < lo ? a : lo;
+      hi = b > hi ? b : hi;
+    }
+    r = (float)hi - (float)lo;
+    R[c] = r;
   }
-  const int an = rank < n_a ? 1 : 0;
-  flag[c] = an;
   __syncthreads();
-  int below = 0;
-  for (int j = 0; j < c; ++j) below += flag[j];
-  const int pos = an ? below : n_a + (c - below);
-  perm[hd * D + pos] = (uint8_t)c;
+  int an = 0;
+  if (part == 0) {
+    int rank = 0;
+    for (int j = 0; j < D; ++j) {
+      const float rj = R[j];
+      rank += (rj > r || (rj == r && j < c)) ? 1 : 0;
+    }
+    an = rank < n_a ? 1 : 0;
+    flag[c] = an;
+  }
+  __syncthreads();
+  if (part == 0) {
+    int below = 0;
+    for (int j = 0; j < c; ++j) below += flag[j];
+    const int pos = an ? below : n_a + (c - below);
+    perm[hd * D + pos] = (uint8_t)c;
+  }
 }
 
 // ---------------------------------------------------------------------------
@@ -258,7 +277,7 @@ hipError_t launch_quantize_keys(const Geom& g, const void* K, uint8_t* packed, v
     hipLaunchKernelGGL(k_range_kernel, gr1, dim3(256), 0, st, reinterpret_cast<const u32x4*>(K),
                        g.T, g.range_chunks, w);
   if (stages & 2u)
-    hipLaunchKernelGGL(k_select_kernel, dim3((unsigned)g.nheads), dim3(128), 0, st, w,
+    hipLaunchKernelGGL(k_select_kernel, dim3((unsigned)g.nheads), dim3(1024), 0, st, w,
                        g.range_chunks, g.n_a, packed + g.k_perm);
   dim3 gr3(g.ng, (unsigned)g.nheads);
   if (stages & 4u)

@@ -11,9 +11,9 @@ __device__ __forceinline__ uint32_t fkey(float f) {
   return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
 }
 
-// Exclusive scan of one int per thread over a 1024-thread block; also returns
-// the block total.  `sw` is LDS scratch of 16 ints.
-__device__ __forceinline__ int block_exscan_1024(int v, int* sw, int* total) {
+// Exclusive scan of one int per thread over a 256-thread block; `sw` is LDS
+// scratch of 4 ints.  Returns the exclusive prefix, *total the block sum.
+__device__ __forceinline__ int block_exscan_256(int v, int* sw, int* total) {
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
   int inc = v;
 #pragma unroll
@@ -26,7 +26,7 @@ __device__ __forceinline__ int block_exscan_1024(int v, int* sw, int* total) {
   __syncthreads();
   int base = 0, tot = 0;
 #pragma unroll
-  for (int i = 0; i < 16; ++i) {
+  for (int i = 0; i < 4; ++i) {
     const int s = sw[i];
     base += (i < wv) ? s : 0;
     tot += s;
@@ -36,95 +36,235 @@ __device__ __forceinline__ int block_exscan_1024(int v, int* sw, int* total) {
 }
 
 // ---------------------------------------------------------------------------
-// One workgroup of 1024 threads per sequence.  Produces, in the value buffer,
-// MASK (bit per token), RANK (protected tokens before each group) and IDX
-// (ascending list).  With scores: the n_s largest by (score desc, index asc),
-// found by a 4 x 8-bit radix select on the ordered keys; with a given index
-// list: the list itself.
+// Protected-token selection, several workgroups per sequence.
+//
+// From scores: the n_s largest by (score desc, index asc) via a 3-level radix
+// select on the ordered 32-bit keys (11 + 11 + 10 bits).  Each level is one
+// launch: every workgroup histograms its slice of SEL_SLICE tokens in LDS and
+// adds it to a global histogram; the workgroup that finishes last (atomic
+// ticket, nobody waits) scans the histogram from the top and narrows the
+// prefix.  Then a counting launch (selected / tied elements per slice, last
+// workgroup turns them into exclusive prefixes) and a marking launch that
+// writes MASK, RANK and IDX.  From an index list: MASK is zeroed and set by
+// atomics, then the same counting and marking launches run on the mask.
+//
+// Workspace (ints): per sequence b
+//   tick[b][4]                 completion tickets of the 3 levels + counting
+//   st[b][4]                   prefix, remaining, (unused)
+//   hist[b][3][2048]
+//   cnt[b][nslice][2]          selected, tied          (per slice)
+//   pre[b][nslice][2]          exclusive prefixes of the above
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(1024) void v_select_kernel(const float* __restrict__ scores,
-                                                        const int32_t* __restrict__ idx_in,
-                                                        int T, int ng, int n_s,
-                                                        int32_t* __restrict__ idx_out,
-                                                        uint32_t* __restrict__ mask,
-                                                        uint32_t* __restrict__ rank) {
-  const int b = blockIdx.x;
-  const int tid = threadIdx.x;
-  __shared__ int hist[256];
-  __shared__ int sw[16];
-  __shared__ uint32_t s_prefix;
-  __shared__ int s_remaining;
-  uint32_t* mk = mask + (size_t)b * ng;
-  uint32_t* rk = rank + (size_t)b * ng;
-  int32_t* io = idx_out + (size_t)b * n_s;
-  const int gpt = (ng + 1023) / 1024;            // groups per thread (contiguous segment)
-  const int g0 = min(ng, tid * gpt), g1 = min(ng, g0 + gpt);
+constexpr int SEL_SLICE = 8192;                  // tokens per workgroup = 256 groups
+constexpr int SEL_BINS = 2048;
 
-  if (scores) {
-    const float* sc = scores + (size_t)b * T;
-    if (tid == 0) { s_prefix = 0; s_remaining = n_s; }
-    uint32_t pmask = 0;
-    for (int pass = 3; pass >= 0; --pass) {
-      for (int i = tid; i < 256; i += 1024) hist[i] = 0;
-      __syncthreads();
-      const uint32_t prefix = s_prefix;
-      for (int t = tid; t < T; t += 1024) {
-        const uint32_t k = fkey(sc[t]);
-        if ((k & pmask) == prefix) atomicAdd(&hist[(k >> (8 * pass)) & 255], 1);
-      }
-      __syncthreads();
-      if (tid == 0) {
-        int rem = s_remaining, bin = 255;
-        for (; bin > 0; --bin) {
-          if (hist[bin] >= rem) break;
-          rem -= hist[bin];
-        }
-        s_prefix = prefix | ((uint32_t)bin << (8 * pass));
-        s_remaining = rem;
-      }
-      pmask |= 0xFFu << (8 * pass);
-      __syncthreads();
-    }
-    const uint32_t kth = s_prefix;
-    const int take_eq = s_remaining;             // equal-to-kth elements to take, lowest index first
-    int neq = 0;
-    for (int t = g0 * G; t < g1 * G; ++t) neq += (fkey(sc[t]) == kth) ? 1 : 0;
-    int tot;
-    int eq_before = block_exscan_1024(neq, sw, &tot);
-    for (int g = g0; g < g1; ++g) {
-      uint32_t w = 0;
-      for (int j = 0; j < G; ++j) {
-        const uint32_t k = fkey(sc[g * G + j]);
-        bool sel = k > kth;
-        if (k == kth) { sel = eq_before < take_eq; ++eq_before; }
-        w |= sel ? (1u << j) : 0u;
-      }
-      mk[g] = w;
-    }
-  } else {
-    for (int g = tid; g < ng; g += 1024) mk[g] = 0;
-    __syncthreads();
-    for (int i = tid; i < n_s; i += 1024) {
-      const int t = idx_in[(size_t)b * n_s + i];
-      atomicOr(&mk[t >> 5], 1u << (t & 31));
-    }
+struct SelWs {
+  int* tick; int* st; int* hist; int* cnt; int* pre;
+  int nslice;
+};
+
+__host__ __device__ inline size_t sel_ws_ints(int B, int nslice) {
+  return (size_t)B * (4 + 4 + 3 * SEL_BINS + 4 * (size_t)nslice);
+}
+
+__device__ __host__ inline SelWs sel_ws(void* ws, int B, int nslice) {
+  SelWs w;
+  int* p = reinterpret_cast<int*>(ws);
+  w.tick = p;  p += (size_t)B * 4;
+  w.st = p;    p += (size_t)B * 4;
+  w.hist = p;  p += (size_t)B * 3 * SEL_BINS;
+  w.cnt = p;   p += (size_t)B * nslice * 2;
+  w.pre = p;
+  w.nslice = nslice;
+  return w;
+}
+
+__global__ __launch_bounds__(256) void v_sel_init_kernel(int* __restrict__ ws, size_t n_ints,
+                                                         int B, int n_s,
+                                                         uint32_t* __restrict__ mask, size_t n_mask) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n_ints) {
+    // st[b][1] starts as "remaining = n_s"; everything else is 0
+    const size_t st0 = (size_t)B * 4;
+    int v = 0;
+    if (i >= st0 && i < st0 + (size_t)B * 4 && ((i - st0) & 3) == 1) v = n_s;
+    ws[i] = v;
+  }
+  if (mask && i < n_mask) mask[i] = 0;
+}
+
+__device__ __forceinline__ int ld_dev(const int* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+template <int LEVEL>
+__global__ __launch_bounds__(256) void v_sel_level_kernel(const float* __restrict__ scores, int T,
+                                                          SelWs w) {
+  constexpr int SHIFT = LEVEL == 0 ? 21 : (LEVEL == 1 ? 10 : 0);
+  constexpr int NB = LEVEL == 2 ? 1024 : 2048;
+  constexpr uint32_t PMASK = LEVEL == 0 ? 0u : (LEVEL == 1 ? 0xFFE00000u : 0xFFFFFC00u);
+  const int b = blockIdx.y, slice = blockIdx.x, tid = threadIdx.x;
+  __shared__ int h[SEL_BINS];
+  __shared__ int cum[256];
+  __shared__ int s_last;
+  for (int i = tid; i < NB; i += 256) h[i] = 0;
+  const uint32_t prefix = (uint32_t)ld_dev(&w.st[b * 4 + 0]);
+  __syncthreads();
+  const float* sc = scores + (size_t)b * T;
+  const int t0 = slice * SEL_SLICE, t1 = min(T, t0 + SEL_SLICE);
+  for (int t = t0 + tid; t < t1; t += 256) {
+    const uint32_t k = fkey(sc[t]);
+    if ((k & PMASK) == prefix) atomicAdd(&h[(k >> SHIFT) & (NB - 1)], 1);
   }
   __syncthreads();
-  int cnt = 0;
-  // device-scope loads: the words may have been set by other waves' atomics
-  for (int g = g0; g < g1; ++g)
-    cnt += __popc(__hip_atomic_load(&mk[g], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+  int* gh = w.hist + ((size_t)b * 3 + LEVEL) * SEL_BINS;
+  for (int i = tid; i < NB; i += 256)
+    if (h[i]) atomicAdd(&gh[i], h[i]);
+  __threadfence();
+  __syncthreads();
+  if (tid == 0) s_last = (atomicAdd(&w.tick[b * 4 + LEVEL], 1) == (int)gridDim.x - 1) ? 1 : 0;
+  __syncthreads();
+  if (!s_last) return;
+  __threadfence();
+  // last workgroup of this sequence: find the bin that holds the remaining-th largest key
+  constexpr int PER = NB / 256;
+  int mine = 0;
+#pragma unroll
+  for (int i = 0; i < PER; ++i) mine += ld_dev(&gh[tid * PER + i]);
+  cum[tid] = mine;
+  __syncthreads();
+  if (tid == 0) {
+    int rem = ld_dev(&w.st[b * 4 + 1]);
+    int th = 255;
+    for (; th > 0; --th) {
+      if (cum[th] >= rem) break;
+      rem -= cum[th];
+    }
+    int bin = th * PER + PER - 1;
+    for (; bin > th * PER; --bin) {
+      const int c = ld_dev(&gh[bin]);
+      if (c >= rem) break;
+      rem -= c;
+    }
+    w.st[b * 4 + 0] = (int)(prefix | ((uint32_t)bin << SHIFT));
+    w.st[b * 4 + 1] = rem;
+  }
+}
+
+// Flags of one 32-token group: bit j set = token selected-or-tied information.
+// FROM_MASK = false: sel = key > kth, tie = key == kth.  true: sel = mask bits.
+template <bool FROM_MASK>
+__device__ __forceinline__ void group_flags(const float* sc, const uint32_t* mk, int g,
+                                            uint32_t kth, uint32_t* sel, uint32_t* tie) {
+  if (FROM_MASK) {
+    *sel = __hip_atomic_load(&mk[g], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    *tie = 0;
+  } else {
+    uint32_t s = 0, e = 0;
+    const float4* p = reinterpret_cast<const float4*>(sc + (size_t)g * G);
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      const float4 v = p[q];
+      const float x[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const uint32_t k = fkey(x[j]);
+        s |= (k > kth) ? (1u << (4 * q + j)) : 0u;
+        e |= (k == kth) ? (1u << (4 * q + j)) : 0u;
+      }
+    }
+    *sel = s;
+    *tie = e;
+  }
+}
+
+template <bool FROM_MASK>
+__global__ __launch_bounds__(256) void v_sel_count_kernel(const float* __restrict__ scores,
+                                                          const uint32_t* __restrict__ mask, int T,
+                                                          int ng, SelWs w) {
+  const int b = blockIdx.y, slice = blockIdx.x, tid = threadIdx.x;
+  __shared__ int sw[4];
+  __shared__ int s_last;
+  const int g = slice * (SEL_SLICE / G) + tid;
+  uint32_t sel = 0, tie = 0;
+  const uint32_t kth = (uint32_t)ld_dev(&w.st[b * 4 + 0]);
+  if (g < ng) group_flags<FROM_MASK>(scores + (size_t)b * T, mask + (size_t)b * ng, g, kth, &sel, &tie);
+  int tot_s, tot_e;
+  block_exscan_256(__popc(sel), sw, &tot_s);
+  block_exscan_256(__popc(tie), sw, &tot_e);
+  if (tid == 0) {
+    w.cnt[((size_t)b * w.nslice + slice) * 2 + 0] = tot_s;
+    w.cnt[((size_t)b * w.nslice + slice) * 2 + 1] = tot_e;
+    __threadfence();
+    s_last = (atomicAdd(&w.tick[b * 4 + 3], 1) == (int)gridDim.x - 1) ? 1 : 0;
+  }
+  __syncthreads();
+  if (!s_last) return;
+  __threadfence();
+  if (tid == 0) {
+    int as = 0, ae = 0;
+    for (int i = 0; i < w.nslice; ++i) {
+      w.pre[((size_t)b * w.nslice + i) * 2 + 0] = as;
+      w.pre[((size_t)b * w.nslice + i) * 2 + 1] = ae;
+      as += ld_dev(&w.cnt[((size_t)b * w.nslice + i) * 2 + 0]);
+      ae += ld_dev(&w.cnt[((size_t)b * w.nslice + i) * 2 + 1]);
+    }
+  }
+}
+
+template <bool FROM_MASK>
+__global__ __launch_bounds__(256) void v_sel_mark_kernel(const float* __restrict__ scores, int T,
+                                                         int ng, int n_s, SelWs w,
+                                                         int32_t* __restrict__ idx_out,
+                                                         uint32_t* __restrict__ mask,
+                                                         uint32_t* __restrict__ rank) {
+  const int b = blockIdx.y, slice = blockIdx.x, tid = threadIdx.x;
+  __shared__ int sw[4];
+  const int g = slice * (SEL_SLICE / G) + tid;
+  uint32_t sel = 0, tie = 0;
+  const uint32_t kth = (uint32_t)w.st[b * 4 + 0];
+  const int take_eq = w.st[b * 4 + 1];            // tied elements to take, lowest index first
+  uint32_t* mk = mask + (size_t)b * ng;
+  if (g < ng) group_flags<FROM_MASK>(scores + (size_t)b * T, mk, g, kth, &sel, &tie);
   int tot;
-  int before = block_exscan_1024(cnt, sw, &tot);
-  for (int g = g0; g < g1; ++g) {
-    uint32_t w = __hip_atomic_load(&mk[g], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    rk[g] = (uint32_t)before;
-    while (w) {
-      const int j = __ffs(w) - 1;
-      w &= w - 1;
+  // ties: take those whose (global, index-ordered) tie number is below take_eq
+  int tie_before = w.pre[((size_t)b * w.nslice + slice) * 2 + 1] +
+                   block_exscan_256(__popc(tie), sw, &tot);
+  uint32_t e = tie;
+  while (e) {
+    const int j = __ffs(e) - 1;
+    e &= e - 1;
+    if (tie_before < take_eq) sel |= 1u << j;
+    ++tie_before;
+  }
+  // number of protected tokens before this group: selected-above-kth before
+  // the slice + ties taken before the slice + the same inside the slice
+  const int ties_before_slice = min(w.pre[((size_t)b * w.nslice + slice) * 2 + 1], take_eq);
+  int before = w.pre[((size_t)b * w.nslice + slice) * 2 + 0] + (FROM_MASK ? 0 : ties_before_slice) +
+               block_exscan_256(__popc(sel), sw, &tot);
+  if (g < ng) {
+    if (!FROM_MASK) mk[g] = sel;
+    rank[(size_t)b * ng + g] = (uint32_t)before;
+    int32_t* io = idx_out + (size_t)b * n_s;
+    uint32_t s = sel;
+    while (s) {
+      const int j = __ffs(s) - 1;
+      s &= s - 1;
       if (before < n_s) io[before] = g * G + j;
       ++before;
     }
+  }
+}
+
+__global__ __launch_bounds__(256) void v_sel_scatter_kernel(const int32_t* __restrict__ idx_in,
+                                                            int n_s, int ng,
+                                                            uint32_t* __restrict__ mask) {
+  const int b = blockIdx.y;
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < n_s) {
+    const int t = idx_in[(size_t)b * n_s + i];
+    if (t >= 0 && t < ng * G)                       // an index outside the cache is ignored
+      atomicOr(&mask[(size_t)b * ng + (t >> 5)], 1u << (t & 31));
   }
 }
 
@@ -166,21 +306,27 @@ __global__ __launch_bounds__(128) void v_encode_kernel(const u32x4* __restrict__
   const int n = 32 - __popc(m);
   const float s = n > 0 ? sum / (float)n : 0.0f;
   const float alpha = gamma * s;
-  uint16_t* rec16 = reinterpret_cast<uint16_t*>(rec4);
+  // channel c = 16 m + r lives in word (kb, r, m >> 1); its 8 token slots fill
+  // one byte of each half-word: byte (m & 1) holds even slots, byte 2 + (m & 1) odd ones
+  uint8_t* rec8 = reinterpret_cast<uint8_t*>(rec4);
+  const int r16 = tid & 15, mt = tid >> 4;
 #pragma unroll
   for (int kb = 0; kb < 4; ++kb) {
-    uint32_t w = 0;
+    uint32_t ev = 0, od = 0;
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
       const int t = (j < 4) ? 4 * kb + j : 16 + 4 * kb + (j - 4);
       const bool keep = !((m >> t) & 1u);
       const uint32_t nz = (keep && (x[t] > alpha || x[t] < -alpha)) ? 1u : 0u;
       const uint32_t ng_ = (keep && x[t] < -alpha) ? 1u : 0u;
-      w |= (nz | (ng_ << 1)) << (8 * (j & 1) + 2 * (j >> 1));
+      const uint32_t f = (nz | (ng_ << 1)) << (2 * (j >> 1));
+      if (j & 1) od |= f; else ev |= f;
     }
-    rec16[(kb * 16 + (tid & 15)) * 8 + (tid >> 4)] = (uint16_t)w;
+    uint8_t* wbytes = rec8 + ((kb * 16 + r16) * 4 + (mt >> 1)) * 4;
+    wbytes[mt & 1] = (uint8_t)ev;
+    wbytes[2 + (mt & 1)] = (uint8_t)od;
   }
-  reinterpret_cast<_Float16*>(rec4)[512 + tid] = (_Float16)s;
+  reinterpret_cast<_Float16*>(rec4)[512 + r16 * 8 + mt] = (_Float16)s;
   __syncthreads();
   u32x4* dst = reinterpret_cast<u32x4*>(rec_out + ((hd * ng) + g) * (long long)VREC);
   if (tid < VREC / 16) dst[tid] = rec4[tid];
@@ -194,16 +340,43 @@ __global__ __launch_bounds__(128) void v_encode_kernel(const u32x4* __restrict__
   }
 }
 
+size_t values_ws_bytes(const Geom& g) {
+  const int nslice = (g.T + SEL_SLICE - 1) / SEL_SLICE;
+  return align256(sel_ws_ints(g.B, nslice > 0 ? nslice : 1) * sizeof(int)) + 256;
+}
+
 hipError_t launch_quantize_values(const Geom& g, float gamma, const void* V, const float* scores,
-                                  const int32_t* idx, uint8_t* packed, unsigned stages,
-                                  hipStream_t st) {
+                                  const int32_t* idx, uint8_t* packed, void* ws,
+                                  unsigned stages, hipStream_t st) {
   if (g.T == 0) return hipSuccess;
   uint32_t* mask = reinterpret_cast<uint32_t*>(packed + g.v_mask);
   uint32_t* rank = reinterpret_cast<uint32_t*>(packed + g.v_rank);
   // stages: bit 0 protected-token selection, bit 1 coding pass
   if (g.n_s > 0 && (stages & 1u)) {
-    hipLaunchKernelGGL(v_select_kernel, dim3(g.B), dim3(1024), 0, st, scores, idx, g.T, g.ng,
-                       g.n_s, reinterpret_cast<int32_t*>(packed + g.v_idx), mask, rank);
+    const int nslice = (g.T + SEL_SLICE - 1) / SEL_SLICE;
+    SelWs w = sel_ws(ws, g.B, nslice);
+    const size_t n_ints = sel_ws_ints(g.B, nslice);
+    const size_t n_mask = (size_t)g.B * g.ng;
+    const size_t n_init = scores ? n_ints : (n_ints > n_mask ? n_ints : n_mask);
+    int32_t* idx_out = reinterpret_cast<int32_t*>(packed + g.v_idx);
+    dim3 gs(nslice, g.B);
+    hipLaunchKernelGGL(v_sel_init_kernel, dim3((unsigned)((n_init + 255) / 256)), dim3(256), 0, st,
+                       reinterpret_cast<int*>(ws), n_ints, g.B, g.n_s, scores ? nullptr : mask,
+                       n_mask);
+    if (scores) {
+      hipLaunchKernelGGL(v_sel_level_kernel<0>, gs, dim3(256), 0, st, scores, g.T, w);
+      hipLaunchKernelGGL(v_sel_level_kernel<1>, gs, dim3(256), 0, st, scores, g.T, w);
+      hipLaunchKernelGGL(v_sel_level_kernel<2>, gs, dim3(256), 0, st, scores, g.T, w);
+      hipLaunchKernelGGL(v_sel_count_kernel<false>, gs, dim3(256), 0, st, scores, mask, g.T, g.ng, w);
+      hipLaunchKernelGGL(v_sel_mark_kernel<false>, gs, dim3(256), 0, st, scores, g.T, g.ng, g.n_s,
+                         w, idx_out, mask, rank);
+    } else {
+      hipLaunchKernelGGL(v_sel_scatter_kernel, dim3((g.n_s + 255) / 256, g.B), dim3(256), 0, st,
+                         idx, g.n_s, g.ng, mask);
+      hipLaunchKernelGGL(v_sel_count_kernel<true>, gs, dim3(256), 0, st, scores, mask, g.T, g.ng, w);
+      hipLaunchKernelGGL(v_sel_mark_kernel<true>, gs, dim3(256), 0, st, scores, g.T, g.ng, g.n_s, w,
+                         idx_out, mask, rank);
+    }
   }
   dim3 gr(g.ng, (unsigned)g.nheads);
   if (stages & 2u)

@@ -6,8 +6,9 @@ namespace vidkv {
 hipError_t launch_quantize_keys(const Geom& g, const void* K, uint8_t* packed, void* ws,
                                 unsigned stages, hipStream_t st);
 hipError_t launch_quantize_values(const Geom& g, float gamma, const void* V, const float* scores,
-                                  const int32_t* idx, uint8_t* packed, unsigned stages,
-                                  hipStream_t st);
+                                  const int32_t* idx, uint8_t* packed, void* ws,
+                                  unsigned stages, hipStream_t st);
+size_t values_ws_bytes(const Geom& g);
 hipError_t launch_decode_attention(const Geom& g, int layer, float scale, const void* q,
                                    const uint8_t* pk, const uint8_t* pv, const void* ktail,
                                    const void* vtail, int cap, const int32_t* tail_len, void* out,
@@ -17,7 +18,7 @@ int attn_num_splits(const Geom& g);
 static size_t ws_keys(const Geom& g) {
   return align256((size_t)g.nheads * g.range_chunks * 2 * D * sizeof(_Float16)) + 256;
 }
-static size_t ws_values(const Geom&) { return 256; }
+static size_t ws_values(const Geom& g) { return values_ws_bytes(g); }
 static size_t ws_attn(const Geom& g) {
   return align256((size_t)(attn_num_splits(g) + 1) * g.B * g.Hq * (D + 2) * sizeof(float)) + 256;
 }
@@ -88,12 +89,13 @@ vidkv_status vidkv_quantize_values_stages(const vidkv_params* p, const void* V,
   if (g.nheads > 65535) return VIDKV_ESHAPE;
   if (g.n_s > 0 && ((saliency != nullptr) == (salient_idx != nullptr))) return VIDKV_EINVAL;
   if (!(p->gamma >= 0.0f) || !(p->gamma < 1e30f)) return VIDKV_EINVAL;
-  if (!aligned(V, 16) || !aligned(packed, 256) || !aligned(saliency, 4) || !aligned(salient_idx, 4))
+  if (!aligned(V, 16) || !aligned(packed, 256) || !aligned(ws, 256) || !aligned(saliency, 16) ||
+      !aligned(salient_idx, 4))
     return VIDKV_EINVAL;
   if (packed_bytes < g.v_total || ws_bytes < ws_values(g)) return VIDKV_ENOSPACE;
   const hipError_t e =
       launch_quantize_values(g, p->gamma, V, g.n_s > 0 ? saliency : nullptr,
-                             g.n_s > 0 ? salient_idx : nullptr, static_cast<uint8_t*>(packed),
+                             g.n_s > 0 ? salient_idx : nullptr, static_cast<uint8_t*>(packed), ws,
                              stages, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? VIDKV_OK : VIDKV_EHIP;
 }

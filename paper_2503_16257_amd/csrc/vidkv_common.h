@@ -10,10 +10,11 @@
 //                                            bit 8+e: sign(Im X[k]) (k>=1) / sign(Re X[16]) (k=0)
 //     +12 n_a+4 n_n fp16   [n_n/8][2][8]    s_re, s_im      (Eq. 5)
 // Packed value buffer : [REC LBH x Tq/32 x 1280][IDX][MASK][RANK][ROWS]
-//   record: uint16 [4 kb][16 r][8 m] trits of channel 16 m + r, 8 token slots
-//           (slot j: token 4 kb + j for j<4, 16 + 4 kb + j-4 otherwise) at bit
-//           8 (j&1) + 2 (j>>1): nonzero flag, then negative flag;
-//           then fp16 [128] s (Eq. 6).
+//   record: uint32 [4 kb][16 r][4 mp]: word (kb, r, mp) holds 8 token slots of the
+//           channels 16 m + r, m = 2 mp + mh (slot j: token 4 kb + j for j<4,
+//           16 + 4 kb + j-4 otherwise); field of (mh, j) at bit 8 mh + 16 (j&1) +
+//           2 (j>>1): nonzero flag, then negative flag;
+//           then fp16 [16 r][8 m] s (Eq. 6) of channel 16 m + r.
 // Every section starts on a 256-byte boundary.
 #pragma once
 

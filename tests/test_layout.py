@@ -99,17 +99,23 @@ def test_value_round_trip_bits_and_positions():
     c2, s2 = LY.unpack_value_head(by)
     np.testing.assert_array_equal(c2, codes)
     np.testing.assert_array_equal(s2, s16)
-    # hand position: channel 35 (m=2, r=3), token 17 -> kb 0, slot 5 -> bits 12 (nz), 13 (neg)
+    # hand position: channel 35 (m=2 -> mp 1, mh 0; r=3), token 17 -> kb 0, slot 5
+    # -> field at bit 8*0 + 16*1 + 2*2 = 20 (nz), 21 (neg) of word (0, 3, 1)
     z = np.zeros((1, 128, 32), dtype=np.int8); z[0, 35, 17] = -1
     b = LY.pack_value_head(z, np.zeros((1, 128), np.float16))
-    word = (0 * 16 + 3) * 8 + 2
+    word = (0 * 16 + 3) * 4 + 1
     nzb = {int(i): int(b[0, i]) for i in np.nonzero(b[0])[0]}
-    assert nzb == {2 * word + 1: 0x30}
-    # token 6 of channel 0 -> kb 1, slot 2 -> bit 2 only for +1
-    z[:] = 0; z[0, 0, 6] = 1
+    assert nzb == {4 * word + 2: 0x30}
+    # token 6 of channel 16 (m=1 -> mp 0, mh 1; r=0) -> kb 1, slot 2 -> bit 8 + 0 + 2 = 10, +1 only
+    z[:] = 0; z[0, 16, 6] = 1
     b = LY.pack_value_head(z, np.zeros((1, 128), np.float16))
     nzb = {int(i): int(b[0, i]) for i in np.nonzero(b[0])[0]}
-    assert nzb == {2 * ((1 * 16 + 0) * 8 + 0): 0x04}
+    assert nzb == {4 * ((1 * 16 + 0) * 4 + 0) + 1: 0x04}
+    # scale of channel 35 sits at half index r*8 + m = 3*8 + 2
+    sc = np.zeros((1, 128), np.float16); sc[0, 35] = np.float16(2.0)
+    b = LY.pack_value_head(np.zeros((1, 128, 32), np.int8), sc)
+    nzb = {int(i): int(b[0, i]) for i in np.nonzero(b[0])[0]}
+    assert nzb == {1024 + 2 * 26 + 1: 0x40}
     # each 2-bit field of the trit area is one (channel, token)
     seen = set()
     base = np.zeros((1, 1280), dtype=np.uint8)

@@ -88,6 +88,11 @@ def main():
     ap.add_argument("--workload", default="c4_long")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--kernel-iters", type=int, default=20)
+    ap.add_argument("--only", default=None,
+                    choices=["k_range", "k_select", "k_encode", "v_select", "v_encode",
+                             "attn_partial", "attn_merge", "copy"],
+                    help="profiling aid: after set-up run only this kernel --kernel-iters times "
+                         "and exit without the JSON line")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
@@ -165,6 +170,16 @@ def main():
         e1.record()
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / iters * 1e-3          # seconds per call
+
+    if args.only:
+        sel = {"k_range": lambda i: q_keys(i, 1), "k_select": lambda i: q_keys(i, 2),
+               "k_encode": lambda i: q_keys(i, 4), "v_select": lambda i: q_vals(i, 1),
+               "v_encode": lambda i: q_vals(i, 2), "attn_partial": lambda i: attn(i, 1),
+               "attn_merge": lambda i: attn(i, 2),
+               "copy": lambda i: vk.calib_copy(Vs[(i + 1) % NROT], Ks[i % NROT])}[args.only]
+        t = timed(sel, args.kernel_iters)
+        print(f"{args.only}: {t * 1e6:.2f} us per call over {args.kernel_iters} calls", file=sys.stderr)
+        return
 
     # ---- the whole step: W warm-ups, exactly K timed steps
     for i in range(args.warmup):

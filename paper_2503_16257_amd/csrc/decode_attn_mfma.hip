@@ -55,7 +55,7 @@ __device__ __forceinline__ uint32_t pk_mul_bcast_hi(uint32_t a, uint32_t s) {
 constexpr int KCH_MAX = 1536 / 16;     // 16-byte chunks of the largest key record
 
 template <int NA8>
-__global__ __launch_bounds__(256) void attn_mfma_kernel(AttnArgs a) {
+__global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a) {
   constexpr int NA = 8 * NA8, NN = D - NA;
   constexpr int NB = NN / 8;                 // normal 8-channel blocks
   constexpr int U = (NB + 3) / 4;            // K-steps over normal channels
@@ -66,7 +66,8 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnArgs a) {
   constexpr int OFF_AS = 8 * NA, OFF_AZ = 10 * NA, OFF_BITS = 12 * NA, OFF_META = 12 * NA + 4 * NN;
 
   const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // wave-uniform
   const int x16 = lane & 15, kb = lane >> 4;
   const int hcol = x16 & 7, par = x16 >> 3;          // column role: (parity, head)
   const int R = a.rep;
@@ -78,10 +79,19 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnArgs a) {
   __shared__ float ow[4][8][D];              // per wave partial outputs
   __shared__ float mw[4][8], lw[4][8];
 
-  // ---------------- constant operands
+  // ---------------- constant operands (q and the channel permutation via LDS)
+  __shared__ _Float16 qs[8][D];
+  __shared__ uint8_t perm_s[D];
+  {
+    const uint32_t* qsrc = reinterpret_cast<const uint32_t*>(a.q + ((long long)b * a.Hq + kvh * R) * D);
+    for (int i = tid; i < R * (D / 2); i += 256) reinterpret_cast<uint32_t*>(&qs[0][0])[i] = qsrc[i];
+    if (tid < D / 4)
+      reinterpret_cast<uint32_t*>(perm_s)[tid] = reinterpret_cast<const uint32_t*>(a.kperm + hd * D)[tid];
+  }
+  __syncthreads();
   const bool hv = hcol < R;
-  const _Float16* qrow = a.q + ((long long)b * a.Hq + kvh * R + (hv ? hcol : 0)) * D;
-  const uint8_t* perm = a.kperm + hd * D;
+  const _Float16* qrow = &qs[hv ? hcol : 0][0];
+  const uint8_t* perm = perm_s;
   Op Bn[U > 0 ? U : 1];
 #pragma unroll
   for (int u = 0; u < U; ++u) {
@@ -152,8 +162,35 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnArgs a) {
       vspre[grp] = vs[64 + x16];
     }
   };
+  // Protected rows are fetched one pair ahead, their masks two pairs ahead.
+  // The rows of one pair are consecutive in ROWS (rank grows with the token).
+  constexpr int NROW = 8;
+  uint32_t rowcur[NROW], rownext[NROW];
+  uint32_t sm0c = 0, sm1c = 0, rkc = 0, sm0n = 0, sm1n = 0, rkn = 0;
+  const bool has_sal = a.n_s > 0;
+  auto load_masks = [&](int pp, uint32_t& s0, uint32_t& s1, uint32_t& rk) {
+    s0 = s1 = rk = 0;
+    if (has_sal && pp < p_end) {
+      const size_t gi = (size_t)b * a.ng + 2 * pp;
+      s0 = a.vmask[gi];
+      rk = a.vrank[gi];
+      if (2 * pp + 1 < a.ng) s1 = a.vmask[gi + 1];
+    }
+  };
+  auto issue_rows = [&](uint32_t s0, uint32_t s1, uint32_t rk, uint32_t* rows) {
+    const int cnt = __popc(s0) + __popc(s1);
+    const uint32_t* base = reinterpret_cast<const uint32_t*>(a.vrows + (hd * a.n_s + rk) * D) + lane;
+#pragma unroll
+    for (int j = 0; j < NROW; ++j)
+      if (j < cnt) rows[j] = base[j * (D / 2)];
+  };
   int p = p_begin + wave;
   if (p < p_end) prefetch(p);
+  if (has_sal) {
+    load_masks(p, sm0c, sm1c, rkc);
+    load_masks(p + 4, sm0n, sm1n, rkn);
+    if (sm0c | sm1c) issue_rows(sm0c, sm1c, rkc, rowcur);
+  }
 
   for (; p < p_end; p += 4) {
     const bool v1ok = (2 * p + 1) < a.ng;
@@ -167,6 +204,11 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnArgs a) {
       vs[grp] = vspre[grp];
     }
     if (p + 4 < p_end) prefetch(p + 4);
+    uint32_t sm0f = 0, sm1f = 0, rkf = 0;        // masks of the pair after the next one
+    if (has_sal) {
+      if (sm0n | sm1n) issue_rows(sm0n, sm1n, rkn, rownext);
+      load_masks(p + 8, sm0f, sm1f, rkf);
+    }
 
     // ---- normal channels: Y[slot][col] per group, K = channels
     f4 accRe[2], accIm[2];
@@ -274,21 +316,24 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnArgs a) {
 #pragma unroll
       for (int i = 0; i < 8; ++i) sc[i] = -INFINITY;
     }
-    // ---- online softmax, maximum shared by the 4 k-blocks and the 2 parities
+    // ---- online softmax.  The running maximum m_run is shared by the 4 k-blocks
+    // and the 2 parities of a head and is raised lazily: only when some score
+    // exceeds it by more than 8 (p stays below 2^8), which needs no cross-lane
+    // traffic in the common case.
     float mx = sc[0];
 #pragma unroll
     for (int i = 1; i < 8; ++i) mx = fmaxf(mx, sc[i]);
-    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    mx = fmaxf(mx, __shfl_xor(mx, 8, 64));
     if (__any(mx > m_run + 8.0f)) {
+      mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      mx = fmaxf(mx, __shfl_xor(mx, 8, 64));
       const float m_new = fmaxf(m_run, mx);
-      const float al = (m_run == -INFINITY) ? 0.0f : exp2f(m_run - m_new);
+      const float al = (m_run == -INFINITY) ? 0.0f : __builtin_amdgcn_exp2f(m_run - m_new);
 #pragma unroll
       for (int m = 0; m < 8; ++m) o[m] *= al;
       l_run *= al;
       m_run = m_new;
-      if (a.n_s > 0) {
+      if (has_sal) {
         if (lane < 8) al8[wave][lane] = al;
         float ah[8];
 #pragma unroll
@@ -301,7 +346,7 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnArgs a) {
     Op Pp;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      pr[i] = exp2f(sc[i] - m_run);
+      pr[i] = __builtin_amdgcn_exp2f(sc[i] - m_run);
       l_run += pr[i];
       Pp.v[i] = (_Float16)pr[i];
     }
@@ -329,36 +374,41 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnArgs a) {
         o[m] = mma(A, Bp[grp], o[m]);
       }
     }
-    // ---- protected tokens: fp16 rows weighted by the probabilities
-    if (a.n_s > 0) {
-      const uint32_t sm0 = a.vmask[(size_t)b * a.ng + 2 * p];
-      const uint32_t sm1 = v1ok ? a.vmask[(size_t)b * a.ng + 2 * p + 1] : 0u;
-      if (sm0 | sm1) {
+    // ---- protected tokens: fp16 rows (prefetched) weighted by the probabilities
+    if (has_sal) {
+      if (sm0c | sm1c) {
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
           const int t = (i < 4) ? 4 * kb + i : 16 + 4 * kb + (i - 4);
           pl[wave][t][x16] = pr[i];
         }
+        unsigned long long sm = (unsigned long long)sm0c | ((unsigned long long)sm1c << 32);
+        auto add_row = [&](uint32_t bits) {
+          const int t64 = __ffsll((long long)sm) - 1;      // bit t of parity t64 >> 5
+          sm &= sm - 1;
+          const h2 v = bits_h2(bits);
+          const float v0 = (float)v[0], v1 = (float)v[1];
+          const float* pp = &pl[wave][t64 & 31][8 * (t64 >> 5)];
 #pragma unroll
-        for (int grp = 0; grp < 2; ++grp) {
-          uint32_t sm = grp ? sm1 : sm0;
-          if (sm == 0) continue;
-          uint32_t rk = a.vrank[(size_t)b * a.ng + 2 * p + grp];
-          while (sm) {
-            const int t = __ffs(sm) - 1;
-            sm &= sm - 1;
-            const h2 v = *reinterpret_cast<const h2*>(a.vrows + (hd * a.n_s + rk) * D + 2 * lane);
-            const float v0 = (float)v[0], v1 = (float)v[1];
-#pragma unroll
-            for (int h = 0; h < 8; ++h) {
-              const float ph = pl[wave][t][8 * grp + h];
-              osal[h][0] += ph * v0;
-              osal[h][1] += ph * v1;
-            }
-            ++rk;
+          for (int h = 0; h < 8; ++h) {
+            const float ph = pp[h];
+            osal[h][0] += ph * v0;
+            osal[h][1] += ph * v1;
           }
+        };
+#pragma unroll
+        for (int j = 0; j < NROW; ++j)
+          if (sm) add_row(rowcur[j]);
+        uint32_t rk = rkc + NROW;                           // more than NROW rows: fetch on demand
+        while (sm) {
+          add_row(*(reinterpret_cast<const uint32_t*>(a.vrows + (hd * a.n_s + rk) * D) + lane));
+          ++rk;
         }
       }
+      sm0c = sm0n; sm1c = sm1n; rkc = rkn;
+      sm0n = sm0f; sm1n = sm1f; rkn = rkf;
+#pragma unroll
+      for (int j = 0; j < NROW; ++j) rowcur[j] = rownext[j];
     }
   }
 

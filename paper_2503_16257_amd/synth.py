@@ -181,3 +181,39 @@ def values(w: Workload) -> np.ndarray:
     for hd in range(w.n_heads):
         out[hd] = value_head(w, hd)
     return out.reshape(w.L, w.B, w.Hkv, w.T, D)
+
+
+# ---------------------------------------------------------------------------
+# On-device generation for the full-size workloads (GB-sized tensors): same
+# recipe, drawn with torch's device generator so that it takes milliseconds.
+# A head that the oracle should check is simply copied back to the host.
+# ---------------------------------------------------------------------------
+def device_kv(w: Workload, device: str = "cuda:0"):
+    """K, V of a whole workload as [L, B, Hkv, T, 128] fp16 device tensors."""
+    import torch
+    out = []
+    for tensor, is_key in ((T_K, True), (T_V, False)):
+        g = torch.Generator(device=device)
+        g.manual_seed(BASE_SEED + 1000 * w.cfg_id + tensor)
+        x = torch.empty((w.n_heads, w.T, D), dtype=torch.float16, device=device)
+        per = max(1, (1 << 27) // max(w.T * D, 1))           # heads per 128M-element chunk
+        for h0 in range(0, w.n_heads, per):
+            h1 = min(w.n_heads, h0 + per)
+            y = torch.randn((h1 - h0, w.T, D), generator=g, device=device)
+            if w.dist == "toy":
+                if is_key:
+                    for hd in range(h0, h1):
+                        y[hd - h0][:, torch.from_numpy(outlier_channels(w, hd)).to(device)] *= 15.0
+            else:
+                y += 0.5 * torch.randn((h1 - h0, 1, D), generator=g, device=device)
+                if is_key:
+                    for hd in range(h0, h1):
+                        ch = torch.from_numpy(outlier_channels(w, hd)).to(device)
+                        z = torch.randn((w.T, len(ch)), generator=g, device=device)
+                        e = -torch.log(torch.rand((w.T, len(ch)), generator=g, device=device)
+                                       .clamp_min(1e-30))     # chi^2_2 / 2
+                        y[hd - h0][:, ch] += 10.0 * z / torch.sqrt(e)     # Student-t, 2 dof
+            x[h0:h1] = y.clamp_(-60000.0, 60000.0).to(torch.float16)
+            del y
+        out.append(x.view(w.L, w.B, w.Hkv, w.T, D))
+    return out[0], out[1]

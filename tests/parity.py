@@ -67,8 +67,19 @@ class GpuRun:
         vk.quantize_keys(self.p, self.K, self.pk, self.ws)
         vk.quantize_values(self.p, self.V, self.pv, self.ws, saliency=self.sal, salient_idx=self.idx)
         torch.cuda.synchronize()
-        self.pk_np = self.pk.cpu().numpy()
-        self.pv_np = self.pv.cpu().numpy()
+        self._pk_np = self._pv_np = None
+
+    @property
+    def pk_np(self):
+        if self._pk_np is None:
+            self._pk_np = self.pk.cpu().numpy()
+        return self._pk_np
+
+    @property
+    def pv_np(self):
+        if self._pv_np is None:
+            self._pv_np = self.pv.cpu().numpy()
+        return self._pv_np
 
     def attention(self, layer, q, K_tail=None, V_tail=None, cap=0, tail_len=None):
         out = torch.empty((self.w.B, self.w.Hq, 128), dtype=torch.float16, device=self.dev)
@@ -78,20 +89,34 @@ class GpuRun:
         torch.cuda.synchronize()
         return out
 
-    # ---- oracle-side decoding of the GPU's buffers
+    # ---- oracle-side decoding of the GPU's buffers (only the bytes of one head travel)
+    @staticmethod
+    def _bytes(t, off, n):
+        return t[off:off + n].cpu().numpy()
+
     def key_record(self, hd):
         w = self.w
-        perm, recs = LY.key_head_views(self.pk_np, w.L, w.B, w.Hkv, w.T, w.n_anom, hd)
+        sec = LY.key_sections(w.L, w.B, w.Hkv, w.T, w.n_anom)
+        rb = LY.key_record_bytes(w.n_anom)
+        ng = w.T // 32
+        perm = self._bytes(self.pk, sec["perm"] + hd * 128, 128)
+        recs = self._bytes(self.pk, sec["rec"] + hd * ng * rb, ng * rb).reshape(ng, rb)
         return LY.unpack_key_head(perm, recs, w.n_anom)
 
     def value_record(self, hd):
         w = self.w
-        codes, s16 = LY.unpack_value_head(LY.value_head_records(self.pv_np, w.L, w.B, w.Hkv, w.T, hd))
-        sec = LY.value_sections(w.L, w.B, w.Hkv, w.T, w.n_salient)
+        ng = w.T // 32
+        recs = self._bytes(self.pv, hd * ng * LY.VREC, ng * LY.VREC).reshape(ng, LY.VREC)
+        codes, s16 = LY.unpack_value_head(recs)
         b = (hd // w.Hkv) % w.B
-        if w.n_salient:
-            idx, mask, rank = LY.unpack_salient(self.pv_np, sec, b, w.T, w.n_salient)
-            rows = LY.salient_rows(self.pv_np, sec, hd, w.n_salient)
+        n_s = w.n_salient
+        if n_s:
+            sec = LY.value_sections(w.L, w.B, w.Hkv, w.T, n_s)
+            idx = self._bytes(self.pv, sec["idx"] + 4 * b * n_s, 4 * n_s).view("<i4")
+            mask = self._bytes(self.pv, sec["mask"] + 4 * b * ng, 4 * ng).view("<u4")
+            rank = self._bytes(self.pv, sec["rank"] + 4 * b * ng, 4 * ng).view("<u4")
+            rows = self._bytes(self.pv, sec["rows"] + 2 * hd * n_s * 128, 2 * n_s * 128) \
+                .view("<f2").reshape(n_s, 128)
         else:
             idx = np.zeros(0, np.int32); mask = rank = None
             rows = np.zeros((0, 128), np.float16)
@@ -142,10 +167,10 @@ def check_values_head(run: GpuRun, hd: int, V_head: np.ndarray, sal_idx: np.ndar
     assert ulp_diff_f16(got["s16"], ref["s16"]) <= 1
     if w.n_salient:
         np.testing.assert_array_equal(got["idx"], sal_idx)
-        sec = LY.value_sections(w.L, w.B, w.Hkv, w.T, w.n_salient)
-        tmp = np.zeros(sec["total"], np.uint8)
-        LY.pack_salient(tmp, sec, 0, w.B, w.T, sal_idx)
-        _, m_ref, r_ref = LY.unpack_salient(tmp, sec, 0, w.T, w.n_salient)
+        small = LY.value_sections(1, 1, 1, w.T, w.n_salient)    # same section formats, tiny buffer
+        tmp = np.zeros(small["total"], np.uint8)
+        LY.pack_salient(tmp, small, 0, 1, w.T, sal_idx)
+        _, m_ref, r_ref = LY.unpack_salient(tmp, small, 0, w.T, w.n_salient)
         np.testing.assert_array_equal(got["mask"], m_ref)
         np.testing.assert_array_equal(got["rank"], r_ref)
         np.testing.assert_array_equal(got["rows"].view(np.uint16), ref["rows"].view(np.uint16))

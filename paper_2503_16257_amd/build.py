@@ -11,12 +11,14 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libvidkv.so")
 
-SOURCES = ["vidkv_api.hip", "quant_keys.hip", "quant_values.hip", "decode_attn.hip",
+SOURCES = ["vidkv_api.hip", "quant_keys.hip", "quant_keys_mfma.hip", "quant_values.hip", "decode_attn.hip",
            "decode_attn_mfma.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     # packed-fp32 VALU forms are kept off for all device code
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # MFMA results go to ordinary VGPRs (no accumulator-register moves)
+    "-mllvm", "-amdgpu-mfma-vgpr-form",
     "-Wall", "-Wno-unused-function",
 ]
 

@@ -1,6 +1,6 @@
 // Shared declarations of the decode-attention kernels.
 #pragma once
-#include "vidkv_common.h"
+#include "mfma_util.h"
 
 namespace vidkv {
 
@@ -24,13 +24,6 @@ struct AttnArgs {
 // One split partial per (split, sequence, query head): o[128], m, l with
 // p = 2^(score2 - m), l = sum p, o = sum p v.
 constexpr int PART_STRIDE = D + 2;
-
-// cos(2 pi j / 32), j = 0..31, rounded to fp32 (quarter-turn values exact).
-static __device__ const float kCosT[32] = {
-    cos32(0),  cos32(1),  cos32(2),  cos32(3),  cos32(4),  cos32(5),  cos32(6),  cos32(7),
-    cos32(8),  cos32(9),  cos32(10), cos32(11), cos32(12), cos32(13), cos32(14), cos32(15),
-    cos32(16), cos32(17), cos32(18), cos32(19), cos32(20), cos32(21), cos32(22), cos32(23),
-    cos32(24), cos32(25), cos32(26), cos32(27), cos32(28), cos32(29), cos32(30), cos32(31)};
 
 // true if the MFMA kernel has an instantiation for this anomalous-channel count
 bool attn_mfma_supported(int n_a);

@@ -23,23 +23,6 @@
 
 namespace vidkv {
 
-typedef _Float16 h8 __attribute__((ext_vector_type(8)));
-typedef float f4 __attribute__((ext_vector_type(4)));
-
-union Op {   // one MFMA operand: 8 halves in 4 VGPRs
-  h8 v;
-  uint32_t u[4];
-  h2 p[4];
-  u32x4 q;
-};
-
-__device__ __forceinline__ f4 mma(const Op& a, const Op& b, f4 c) {
-  return __builtin_amdgcn_mfma_f32_16x16x32_f16(a.v, b.v, c, 0, 0, 0);
-}
-
-__device__ __forceinline__ uint32_t h2_bits(h2 x) { return __builtin_bit_cast(uint32_t, x); }
-__device__ __forceinline__ h2 bits_h2(uint32_t x) { return __builtin_bit_cast(h2, x); }
-
 // packed fp16 multiply of a by the low / high half of s broadcast to both lanes
 __device__ __forceinline__ uint32_t pk_mul_bcast_lo(uint32_t a, uint32_t s) {
   uint32_t d;

@@ -130,141 +130,8 @@ __global__ __launch_bounds__(1024) void k_select_kernel(const _Float16* __restri
   }
 }
 
-// ---------------------------------------------------------------------------
-// 32-point DFT of a real sequence held in registers, via a 16-point complex
-// FFT of z[n] = x[2n] + i x[2n+1] (decimation in frequency, constant-folded
-// twiddles) and the even/odd split.  Forward convention X[k] = sum x[t]
-// exp(-2 pi i k t / 32), unnormalised.  re[0..16], im[0..16] (im[0]=im[16]=0).
-// ---------------------------------------------------------------------------
-__device__ __forceinline__ void rdft32(const float* x, float* re, float* im) {
-  float zr[16], zi[16];
-#pragma unroll
-  for (int n = 0; n < 16; ++n) { zr[n] = x[2 * n]; zi[n] = x[2 * n + 1]; }
-#pragma unroll
-  for (int s = 8; s >= 1; s >>= 1) {
-#pragma unroll
-    for (int b = 0; b < 16; b += 2 * s) {
-#pragma unroll
-      for (int j = 0; j < s; ++j) {
-        const float wr = cos32(j * (16 / s)), wi = -sin32(j * (16 / s));
-        const float ar = zr[b + j], ai = zi[b + j];
-        const float cr = zr[b + j + s], ci = zi[b + j + s];
-        zr[b + j] = ar + cr;
-        zi[b + j] = ai + ci;
-        const float dr = ar - cr, di = ai - ci;
-        zr[b + j + s] = dr * wr - di * wi;
-        zi[b + j + s] = dr * wi + di * wr;
-      }
-    }
-  }
-  // Z[k] sits at index bitrev4(k)
-#define VIDKV_BR4(k) ((((k) & 1) << 3) | (((k) & 2) << 1) | (((k) & 4) >> 1) | (((k) & 8) >> 3))
-#pragma unroll
-  for (int k = 0; k <= 8; ++k) {
-    const int k2 = (16 - k) & 15;
-    const float ar = zr[VIDKV_BR4(k)], ai = zi[VIDKV_BR4(k)];
-    const float br = zr[VIDKV_BR4(k2)], bi = zi[VIDKV_BR4(k2)];
-    // E = (Z[k] + conj Z[16-k]) / 2 ; O = (Z[k] - conj Z[16-k]) / (2 i)
-    const float er = 0.5f * (ar + br), ei = 0.5f * (ai - bi);
-    const float orr = 0.5f * (ai + bi), oi = -0.5f * (ar - br);
-    {
-      const float wr = cos32(k), wi = -sin32(k);
-      re[k] = er + (orr * wr - oi * wi);
-      im[k] = ei + (orr * wi + oi * wr);
-    }
-    if (k >= 1 && k <= 7) {
-      // X[16-k]: E[16-k] = conj E[k], O[16-k] = conj O[k]
-      const float wr = cos32(16 - k), wi = -sin32(16 - k);
-      re[16 - k] = er + (orr * wr + oi * wi);
-      im[16 - k] = -ei + (orr * wi - oi * wr);
-    }
-    if (k == 0) {
-      re[16] = er - orr;
-      im[16] = 0.0f;
-      im[0] = 0.0f;
-    }
-  }
-#undef VIDKV_BR4
-}
-
-// ---------------------------------------------------------------------------
-// Pass 2: code one 32-token group of one head.  grid (ng, nheads), block 128;
-// thread i owns channel perm[i]: i < n_a -> Eq. 4 at 2 bits, else Eq. 5.
-// The 32 x 128 fp16 tile is staged in LDS with 16-byte loads; the record is
-// assembled in LDS and written out with 16-byte stores.
-// ---------------------------------------------------------------------------
-__global__ __launch_bounds__(128) void k_encode_kernel(const u32x4* __restrict__ K,
-                                                       const uint8_t* __restrict__ perm, int T,
-                                                       int ng, int n_a, int krec,
-                                                       uint8_t* __restrict__ rec_out) {
-  const int g = blockIdx.x;
-  const long long hd = blockIdx.y;
-  const int tid = threadIdx.x;
-  __shared__ u32x4 tile4[32 * 16];                 // [32 tokens][128 ch] fp16
-  __shared__ uint32_t rec[1536 / 4];
-  const int n_n = D - n_a;
-
-  const u32x4* src = K + ((hd * T) + (long long)g * G) * 16;
-#pragma unroll
-  for (int i = 0; i < 4; ++i) tile4[tid + 128 * i] = __builtin_nontemporal_load(src + tid + 128 * i);
-  for (int i = tid; i < krec / 4; i += 128) rec[i] = 0;
-  const int ch = perm[hd * D + tid];
-  __syncthreads();
-
-  const _Float16* tile = reinterpret_cast<const _Float16*>(tile4);
-  float x[32];
-#pragma unroll
-  for (int t = 0; t < 32; ++t) x[t] = (float)tile[t * D + ch];
-
-  _Float16* rec16 = reinterpret_cast<_Float16*>(rec);
-  if (tid < n_a) {
-    const int j = tid;
-    float mn = x[0], mx = x[0];
-#pragma unroll
-    for (int t = 1; t < 32; ++t) { mn = fminf(mn, x[t]); mx = fmaxf(mx, x[t]); }
-    const float rng = mx - mn;
-    const float s = rng / 3.0f;
-    const int nq = n_a >> 2;
-#pragma unroll
-    for (int t = 0; t < 32; ++t) {
-      float u = (rng > 0.0f) ? (3.0f * (x[t] - mn)) / rng : 0.0f;
-      u = fminf(fmaxf(rintf(u), 0.0f), 3.0f);
-      const uint32_t code = (uint32_t)u;
-      const int byte = t * nq + (j >> 2);
-      atomicOr(&rec[byte >> 2], code << (8 * (byte & 3) + 2 * (j & 3)));
-    }
-    rec16[4 * n_a + j] = (_Float16)s;       // byte offset 8 n_a
-    rec16[5 * n_a + j] = (_Float16)mn;      // byte offset 10 n_a
-  } else {
-    const int i = tid - n_a;
-    const int blk = i >> 3, e = i & 7;
-    float re[17], im[17];
-    rdft32(x, re, im);
-    float sre = fabsf(re[0]) + fabsf(re[16]);
-    float sim = 0.0f;
-#pragma unroll
-    for (int k = 1; k < 16; ++k) { sre += 2.0f * fabsf(re[k]); sim += 2.0f * fabsf(im[k]); }
-    sre *= (1.0f / 32.0f);
-    sim *= (1.0f / 32.0f);
-    uint32_t* words = rec + 3 * n_a;                       // byte offset 12 n_a
-#pragma unroll
-    for (int k = 0; k < 16; k += 2) {
-      const uint32_t lo0 = !(re[k] < 0.0f) ? 1u : 0u;
-      const uint32_t hi0 = (k == 0) ? (!(re[16] < 0.0f) ? 1u : 0u) : (!(im[k] < 0.0f) ? 1u : 0u);
-      const uint32_t lo1 = !(re[k + 1] < 0.0f) ? 1u : 0u;
-      const uint32_t hi1 = !(im[k + 1] < 0.0f) ? 1u : 0u;
-      const uint32_t w = ((lo0 << e) | (hi0 << (8 + e))) | (((lo1 << e) | (hi1 << (8 + e))) << 16);
-      atomicOr(&words[(blk * 16 + k) >> 1], w);
-    }
-    _Float16* meta = rec16 + 6 * n_a + 2 * n_n;            // byte offset 12 n_a + 4 n_n
-    meta[(blk * 2 + 0) * 8 + e] = (_Float16)sre;
-    meta[(blk * 2 + 1) * 8 + e] = (_Float16)sim;
-  }
-  __syncthreads();
-  u32x4* dst = reinterpret_cast<u32x4*>(rec_out + ((hd * ng) + g) * (long long)krec);
-  const u32x4* rec4 = reinterpret_cast<const u32x4*>(rec);
-  for (int i = tid; i < krec / 16; i += 128) dst[i] = rec4[i];
-}
+// The per-group coding pass (Eq. 4 and Eq. 5) lives in quant_keys_mfma.hip.
+void launch_k_encode(const Geom& g, const void* K, uint8_t* packed, hipStream_t st);
 
 // ---------------------------------------------------------------------------
 // stages: bit 0 range pass, bit 1 channel selection, bit 2 coding pass
@@ -279,10 +146,7 @@ hipError_t launch_quantize_keys(const Geom& g, const void* K, uint8_t* packed, v
   if (stages & 2u)
     hipLaunchKernelGGL(k_select_kernel, dim3((unsigned)g.nheads), dim3(1024), 0, st, w,
                        g.range_chunks, g.n_a, packed + g.k_perm);
-  dim3 gr3(g.ng, (unsigned)g.nheads);
-  if (stages & 4u)
-    hipLaunchKernelGGL(k_encode_kernel, gr3, dim3(128), 0, st, reinterpret_cast<const u32x4*>(K),
-                       packed + g.k_perm, g.T, g.ng, g.n_a, g.krec, packed + g.k_rec);
+  if (stages & 4u) launch_k_encode(g, K, packed, st);
   return hipGetLastError();
 }
 

@@ -1,0 +1,279 @@
+// Key coding pass (Alg. 3): per 32-token group the 2-bit uniform code (Eq. 4)
+// of the anomalous channels and the FFT-based 1-bit code (Eq. 5) of the others.
+//
+// The 32-point DFT along the tokens is a dense contraction, so it runs on
+// v_mfma_f32_16x16x32_f16.  One wave codes one group at a time:
+//  1. The [32 tokens x 128 channels] fp16 tile is loaded straight into MFMA A
+//     operands (row = token, k-slots = 8 consecutive channels).
+//  2. A product with a 0/1 selection matrix gathers 16 channels of the head's
+//     channel permutation and transposes them: the accumulator holds, per lane,
+//     tokens of one channel, which is the operand layout for a contraction over
+//     tokens.  Values are fp16 inputs times 1.0, hence exact.
+//  3. Normal channels: X (16 channels x 32 tokens) times the DFT matrix, split
+//     in three fp16 parts (exact products, fp32 accumulation), in both
+//     orientations: [channel][slot] gives each lane 4 channels of one
+//     coefficient -> sign bits land in the record's word order with one lane
+//     exchange; [slot][channel] gives each lane 8 coefficients of one channel
+//     -> the mean-|.| scales need only a 4-lane sum.
+//  4. Anomalous channels: min / max over the 32 tokens, codes, 4 channels per
+//     byte assembled inside lane quads.
+// The record is assembled in LDS and written with 16-byte stores.
+#include "mfma_util.h"
+
+namespace vidkv {
+
+__device__ __forceinline__ h2 pk_f16(float a, float b) {     // exact for fp16-valued inputs
+  return __builtin_bit_cast(h2, __builtin_amdgcn_cvt_pkrtz(a, b));
+}
+
+constexpr int ENC_GPB = 16;          // groups per workgroup (4 per wave)
+constexpr int ENC_MAXT = 9;          // channel tiles of 16: at most 1 + 8
+
+// NA8T >= 0 fixes n_a = 8 * NA8T at compile time (tile loop fully unrolled);
+// NA8T < 0 takes n_a at run time.
+template <int NA8T>
+__global__ __launch_bounds__(256) void k_encode_mfma_kernel(const u32x4* __restrict__ K,
+                                                            const uint8_t* __restrict__ perm_g,
+                                                            int T, int ng, int n_a_rt, int krec,
+                                                            uint8_t* __restrict__ rec_out) {
+  const int n_a = NA8T >= 0 ? 8 * NA8T : n_a_rt;
+  const long long hd = blockIdx.y;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int x16 = lane & 15, kb = lane >> 4;
+  const int n_n = D - n_a;
+  const int NTa = (n_a + 15) >> 4, NTn = (n_n + 15) >> 4, NT = NTa + NTn;
+  const int nq = n_a >> 2;
+
+  __shared__ u32x4 sel[ENC_MAXT][4][64];     // selection operands per (tile, K-step)
+  __shared__ uint8_t perm_s[D];
+  __shared__ int ksr[ENC_MAXT];              // K-step range of each tile: lo | hi << 8
+  __shared__ u32x4 recbuf[4][1536 / 16];     // per wave: the record being assembled
+
+  if (tid < D / 4)
+    reinterpret_cast<uint32_t*>(perm_s)[tid] = reinterpret_cast<const uint32_t*>(perm_g + hd * D)[tid];
+  __syncthreads();
+  // Channel tile j: anomalous tiles first (16 anomalous channels each, in PERM
+  // order), then normal tiles.  Column c of tile j is PERM entry `li` below.
+  for (int idx = tid; idx < NT * 256; idx += 256) {
+    const int tile = idx >> 8, ks = (idx >> 6) & 3, ln = idx & 63;
+    const int c = ln & 15, kbb = ln >> 4;
+    const bool an = tile < NTa;
+    const int off = an ? 16 * tile + c : 16 * (tile - NTa) + c;
+    const bool valid = an ? off < n_a : off < n_n;
+    const int ch = valid ? perm_s[an ? off : n_a + off] : -1000;
+    const int local = ch - 32 * ks - 8 * kbb;      // k-slot of that channel in this lane, if any
+    u32x4 v;
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+      v[r] = (local == 2 * r ? 0x3C00u : 0u) | (local == 2 * r + 1 ? 0x3C000000u : 0u);
+    sel[tile][ks][ln] = v;
+  }
+  if (tid < NT) {
+    const bool an = tid < NTa;
+    int lo = 3, hi = 0;
+    for (int c = 0; c < 16; ++c) {
+      const int off = an ? 16 * tid + c : 16 * (tid - NTa) + c;
+      if (an ? off < n_a : off < n_n) {
+        const int ks = perm_s[an ? off : n_a + off] >> 5;
+        lo = min(lo, ks);
+        hi = max(hi, ks);
+      }
+    }
+    ksr[tid] = lo | (hi << 8);
+  }
+  __syncthreads();
+
+  // DFT operand: slot x16 of tile tt (tt = 0: Re X[0..15]; tt = 1: Re X[16], Im X[1..15]),
+  // k-slots = tokens.  Entries are 64 * (w/2) * {cos, -sin}(2 pi k t / 32) with
+  // w = 1 for the two real-only bins and 2 otherwise, so that the sum of |D| over
+  // a channel's slots is 1024 * Mean|.| of Eq. 5; positive row scaling does not
+  // change a sign.  Split into three fp16 parts that add up to the fp32 value.
+  Op F[2][3];
+#pragma unroll
+  for (int tt = 0; tt < 2; ++tt) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int t = slot_token(kb, i), k = x16;
+      float w;
+      if (tt == 0) w = kCosT[(k * t) & 31] * (k == 0 ? 32.0f : 64.0f);
+      else         w = (k == 0) ? ((t & 1) ? -32.0f : 32.0f) : -kCosT[(k * t + 24) & 31] * 64.0f;
+      if (w == 0.0f) w = 0.0f;                       // no negative zero
+      const _Float16 a = (_Float16)w;
+      const float r1 = w - (float)a;
+      const _Float16 b = (_Float16)r1;
+      const _Float16 c = (_Float16)(r1 - (float)b);
+      F[tt][0].v[i] = a;
+      F[tt][1].v[i] = b;
+      F[tt][2].v[i] = c;
+    }
+  }
+
+  uint8_t* rec8 = reinterpret_cast<uint8_t*>(&recbuf[wave][0]);
+  uint16_t* rec16 = reinterpret_cast<uint16_t*>(rec8);
+  const int bits_h = 6 * n_a;                        // half-word offsets inside the record
+  const int meta_h = 6 * n_a + 2 * n_n;
+  const int nblk = n_n >> 3;
+
+  const int g_begin = blockIdx.x * ENC_GPB;
+  const int g_end = min(ng, g_begin + ENC_GPB);
+  const u32x4* head = K + hd * (long long)T * 16;
+
+  u32x4 Apre[2][4];
+  auto prefetch = [&](int g) {
+    const u32x4* src = head + (long long)g * G * 16;
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks)
+        Apre[mt][ks] = __builtin_nontemporal_load(src + (16 * mt + x16) * 16 + 4 * ks + kb);
+  };
+  int g = g_begin + wave;
+  if (g < g_end) prefetch(g);
+
+  for (; g < g_end; g += 4) {
+    Op A[2][4];
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) A[mt][ks].q = Apre[mt][ks];
+    if (g + 4 < g_end) prefetch(g + 4);
+
+#pragma unroll
+    for (int j = 0; j < NT; ++j) {
+      const int kr = __builtin_amdgcn_readfirstlane(ksr[j]);
+      const int klo = kr & 255, khi = kr >> 8;
+      // ---- gather + transpose: T[mt] = tokens (rows) x 16 permuted channels (columns)
+      f4 T0 = f4{0.f, 0.f, 0.f, 0.f}, T1 = f4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        if (ks >= klo && ks <= khi) {
+          Op S;
+          S.q = sel[j][ks][lane];
+          T0 = mma(A[0][ks], S, T0);
+          T1 = mma(A[1][ks], S, T1);
+        }
+      }
+      // my column's channel at my 8 token slots, as an operand (exact fp16 values)
+      Op X;
+      X.p[0] = pk_f16(T0[0], T0[1]);
+      X.p[1] = pk_f16(T0[2], T0[3]);
+      X.p[2] = pk_f16(T1[0], T1[1]);
+      X.p[3] = pk_f16(T1[2], T1[3]);
+
+      if (j < NTa) {
+        // ---------------- Eq. 4, 2 bits: z = min, s = (max - min) / 3 over the 32 tokens
+        h2 mn2 = __builtin_elementwise_min(__builtin_elementwise_min(X.p[0], X.p[1]),
+                                           __builtin_elementwise_min(X.p[2], X.p[3]));
+        h2 mx2 = __builtin_elementwise_max(__builtin_elementwise_max(X.p[0], X.p[1]),
+                                           __builtin_elementwise_max(X.p[2], X.p[3]));
+        // min and -max over the 4 lane groups: both are "min" reductions, so one
+        // swap pair serves the two values; a last swap hands both to every lane
+        float lo_f = fminf((float)mn2[0], (float)mn2[1]);
+        float nh_f = -fmaxf((float)mx2[0], (float)mx2[1]);
+        {
+          auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(lo_f), __float_as_uint(nh_f), false, false);
+          const float t = fminf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+          auto q = __builtin_amdgcn_permlane16_swap(__float_as_uint(t), __float_as_uint(t), false, false);
+          const float u = fminf(__uint_as_float(q[0]), __uint_as_float(q[1]));   // rows 0,1: min; rows 2,3: -max
+          auto w = __builtin_amdgcn_permlane32_swap(__float_as_uint(u), __float_as_uint(u), false, false);
+          lo_f = __uint_as_float(w[0]);
+          nh_f = __uint_as_float(w[1]);
+        }
+        const _Float16 lo = (_Float16)lo_f;
+        const float mnf = lo_f, rng = -nh_f - lo_f;
+        const float inv = rng > 0.0f ? 3.0f / rng : 0.0f;
+        uint32_t w0 = 0, w1 = 0;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          float u = ((float)X.v[i] - mnf) * inv;
+          u = fminf(fmaxf(rintf(u), 0.0f), 3.0f);
+          const uint32_t c = (uint32_t)u;
+          if (i < 4) w0 |= c << (8 * i); else w1 |= c << (8 * (i - 4));
+        }
+        // 4 channels of a quad (adjacent lanes) share a byte: channel r in bits 2r, 2r+1
+        w0 <<= 2 * (x16 & 3);
+        w1 <<= 2 * (x16 & 3);
+        w0 |= __shfl_xor(w0, 1, 64);  w1 |= __shfl_xor(w1, 1, 64);
+        w0 |= __shfl_xor(w0, 2, 64);  w1 |= __shfl_xor(w1, 2, 64);
+        const int ja = 16 * j + x16;                 // anomalous index of my column
+        if (ja < n_a) {
+          const int quad = ja >> 2;
+          if ((x16 & 3) == 0) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              rec8[(4 * kb + i) * nq + quad] = (uint8_t)(w0 >> (8 * i));
+              rec8[(16 + 4 * kb + i) * nq + quad] = (uint8_t)(w1 >> (8 * i));
+            }
+          }
+          if (kb == 0) {
+            reinterpret_cast<_Float16*>(rec16)[4 * n_a + ja] = (_Float16)(rng / 3.0f);
+            reinterpret_cast<_Float16*>(rec16)[5 * n_a + ja] = lo;
+          }
+        }
+      } else {
+        // ---------------- Eq. 5: 32-point DFT along tokens, sign bits and mean-|.| scales
+        const int jn = j - NTa;
+        // [channel][slot]: my column = slot x16, my rows = channels 4kb + i of the tile
+        const f4 zero = f4{0.f, 0.f, 0.f, 0.f};
+        f4 sRe = mma(X, F[0][0], zero), sIm = mma(X, F[1][0], zero);
+        sRe = mma(X, F[0][1], sRe);  sIm = mma(X, F[1][1], sIm);
+        sRe = mma(X, F[0][2], sRe);  sIm = mma(X, F[1][2], sIm);
+        // [slot][channel]: my column = channel x16, my rows = slots 4kb + i
+        f4 aRe = mma(F[0][0], X, zero), aIm = mma(F[1][0], X, zero);
+        aRe = mma(F[0][1], X, aRe);  aIm = mma(F[1][1], X, aIm);
+        // sign bits: shift in the IEEE sign of each value, then invert (bit = coef >= 0)
+        uint32_t nb = 0;
+#pragma unroll
+        for (int i = 3; i >= 0; --i) nb = __builtin_amdgcn_alignbit(nb, __float_as_uint(sIm[i]), 31);
+#pragma unroll
+        for (int i = 3; i >= 0; --i) nb = __builtin_amdgcn_alignbit(nb, __float_as_uint(sRe[i]), 31);
+        nb = ~nb & 0xFFu;                           // bits 0-3: Re of channels 4kb+i, bits 4-7: Im
+        // even lane groups hold channels e = 0-3 of a block, odd ones e = 4-7
+        auto nx = __builtin_amdgcn_permlane16_swap(nb, nb, false, false);
+        const uint32_t l4 = nx[0], h4 = nx[1];
+        const uint32_t w16 = (l4 & 0xFu) | ((h4 & 0xFu) << 4) | ((l4 >> 4) << 8) | ((h4 >> 4) << 12);
+        const int blk = 2 * jn + (kb >> 1);
+        if ((kb & 1) == 0 && blk < nblk) rec16[bits_h + blk * 16 + x16] = (uint16_t)w16;
+        // scales: Re X[16] sits in row 0 of the second tile and counts for the real view
+        float sr = fabsf(aRe[0]) + fabsf(aRe[1]) + fabsf(aRe[2]) + fabsf(aRe[3]);
+        float si = fabsf(aIm[0]) + fabsf(aIm[1]) + fabsf(aIm[2]) + fabsf(aIm[3]);
+        if (kb == 0) { sr += fabsf(aIm[0]); si -= fabsf(aIm[0]); }
+        // sum over the 4 lane groups: afterwards rows 0,1 hold the Re total, rows 2,3 the Im total
+        auto r32 = __builtin_amdgcn_permlane32_swap(__float_as_uint(sr), __float_as_uint(si), false, false);
+        const float t2 = __uint_as_float(r32[0]) + __uint_as_float(r32[1]);
+        auto r16 = __builtin_amdgcn_permlane16_swap(__float_as_uint(t2), __float_as_uint(t2), false, false);
+        const float tot = (__uint_as_float(r16[0]) + __uint_as_float(r16[1])) * (1.0f / 1024.0f);
+        const int nidx = 16 * jn + x16;              // normal index of my column
+        if ((kb & 1) == 0 && nidx < n_n) {
+          const int b8 = nidx >> 3, e = nidx & 7;
+          reinterpret_cast<_Float16*>(rec16)[meta_h + (b8 * 2 + (kb >> 1)) * 8 + e] = (_Float16)tot;
+        }
+      }
+    }
+    // ---- the finished record: LDS -> global, 16 bytes per lane
+    u32x4* dst = reinterpret_cast<u32x4*>(rec_out + (hd * ng + g) * (long long)krec);
+    const int nch = krec >> 4;
+    if (lane < nch) dst[lane] = recbuf[wave][lane];
+    if (lane + 64 < nch) dst[lane + 64] = recbuf[wave][lane + 64];
+  }
+}
+
+void launch_k_encode(const Geom& g, const void* K, uint8_t* packed, hipStream_t st) {
+  dim3 grid((g.ng + ENC_GPB - 1) / ENC_GPB, (unsigned)g.nheads);
+  const u32x4* k4 = reinterpret_cast<const u32x4*>(K);
+  const uint8_t* perm = packed + g.k_perm;
+  uint8_t* rec = packed + g.k_rec;
+#define VIDKV_ENC(N) \
+  hipLaunchKernelGGL(k_encode_mfma_kernel<N>, grid, dim3(256), 0, st, k4, perm, g.T, g.ng, g.n_a, g.krec, rec)
+  switch (g.n_a) {
+    case 8:  VIDKV_ENC(1); break;
+    case 16: VIDKV_ENC(2); break;
+    case 32: VIDKV_ENC(4); break;
+    case 64: VIDKV_ENC(8); break;
+    default: VIDKV_ENC(-1); break;
+  }
+#undef VIDKV_ENC
+}
+
+}  // namespace vidkv

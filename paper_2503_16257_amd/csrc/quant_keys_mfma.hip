@@ -3,17 +3,17 @@
 //
 // The 32-point DFT along the tokens is a dense contraction, so it runs on
 // v_mfma_f32_16x16x32_f16.  One wave codes one group at a time:
-//  1. The [32 tokens x 128 channels] fp16 tile is loaded straight into MFMA A
-//     operands (row = token, k-slots = 8 consecutive channels).
-//  2. A product with a 0/1 selection matrix gathers 16 channels of the head's
-//     channel permutation and transposes them: the accumulator holds, per lane,
-//     tokens of one channel, which is the operand layout for a contraction over
-//     tokens.  Values are fp16 inputs times 1.0, hence exact.
+//  1. The [32 tokens x 128 channels] fp16 tile goes global -> registers -> LDS
+//     with 16-byte accesses (rows padded to 272 bytes).
+//  2. Each lane reads, for a tile of 16 channels taken from the head's channel
+//     permutation, its channel at its 8 token slots with 16-bit LDS loads that
+//     fill register halves directly: the MFMA operand of a contraction over
+//     tokens, gathered and transposed for free.
 //  3. Normal channels: X (16 channels x 32 tokens) times the DFT matrix, split
 //     in three fp16 parts (exact products, fp32 accumulation), in both
 //     orientations: [channel][slot] gives each lane 4 channels of one
 //     coefficient -> sign bits land in the record's word order with one lane
-//     exchange; [slot][channel] gives each lane 8 coefficients of one channel
+//     swap; [slot][channel] gives each lane 8 coefficients of one channel
 //     -> the mean-|.| scales need only a 4-lane sum.
 //  4. Anomalous channels: min / max over the 32 tokens, codes, 4 channels per
 //     byte assembled inside lane quads.
@@ -22,12 +22,9 @@
 
 namespace vidkv {
 
-__device__ __forceinline__ h2 pk_f16(float a, float b) {     // exact for fp16-valued inputs
-  return __builtin_bit_cast(h2, __builtin_amdgcn_cvt_pkrtz(a, b));
-}
-
 constexpr int ENC_GPB = 16;          // groups per workgroup (4 per wave)
 constexpr int ENC_MAXT = 9;          // channel tiles of 16: at most 1 + 8
+constexpr int ENC_ROW = 272;         // LDS bytes per token row (256 + 16 of padding)
 
 // NA8T >= 0 fixes n_a = 8 * NA8T at compile time (tile loop fully unrolled);
 // NA8T < 0 takes n_a at run time.
@@ -45,44 +42,20 @@ __global__ __launch_bounds__(256) void k_encode_mfma_kernel(const u32x4* __restr
   const int NTa = (n_a + 15) >> 4, NTn = (n_n + 15) >> 4, NT = NTa + NTn;
   const int nq = n_a >> 2;
 
-  __shared__ u32x4 sel[ENC_MAXT][4][64];     // selection operands per (tile, K-step)
-  __shared__ uint8_t perm_s[D];
-  __shared__ int ksr[ENC_MAXT];              // K-step range of each tile: lo | hi << 8
-  __shared__ u32x4 recbuf[4][1536 / 16];     // per wave: the record being assembled
+  __shared__ u32x4 tile4[4][32 * ENC_ROW / 16];   // per wave: the group's tile
+  __shared__ u32x4 recbuf[4][1536 / 16];          // per wave: the record being assembled
 
-  if (tid < D / 4)
-    reinterpret_cast<uint32_t*>(perm_s)[tid] = reinterpret_cast<const uint32_t*>(perm_g + hd * D)[tid];
-  __syncthreads();
   // Channel tile j: anomalous tiles first (16 anomalous channels each, in PERM
-  // order), then normal tiles.  Column c of tile j is PERM entry `li` below.
-  for (int idx = tid; idx < NT * 256; idx += 256) {
-    const int tile = idx >> 8, ks = (idx >> 6) & 3, ln = idx & 63;
-    const int c = ln & 15, kbb = ln >> 4;
-    const bool an = tile < NTa;
-    const int off = an ? 16 * tile + c : 16 * (tile - NTa) + c;
-    const bool valid = an ? off < n_a : off < n_n;
-    const int ch = valid ? perm_s[an ? off : n_a + off] : -1000;
-    const int local = ch - 32 * ks - 8 * kbb;      // k-slot of that channel in this lane, if any
-    u32x4 v;
+  // order), then normal tiles.  My column's channel in every tile, as a byte
+  // offset inside a token row (an absent column reads channel 0 and is ignored).
+  int chofs[ENC_MAXT];
 #pragma unroll
-    for (int r = 0; r < 4; ++r)
-      v[r] = (local == 2 * r ? 0x3C00u : 0u) | (local == 2 * r + 1 ? 0x3C000000u : 0u);
-    sel[tile][ks][ln] = v;
+  for (int j = 0; j < ENC_MAXT; ++j) {
+    const bool an = j < NTa;
+    const int off = an ? 16 * j + x16 : 16 * (j - NTa) + x16;
+    const bool valid = j < NT && (an ? off < n_a : off < n_n);
+    chofs[j] = valid ? 2 * (int)perm_g[hd * D + (an ? off : n_a + off)] : 0;
   }
-  if (tid < NT) {
-    const bool an = tid < NTa;
-    int lo = 3, hi = 0;
-    for (int c = 0; c < 16; ++c) {
-      const int off = an ? 16 * tid + c : 16 * (tid - NTa) + c;
-      if (an ? off < n_a : off < n_n) {
-        const int ks = perm_s[an ? off : n_a + off] >> 5;
-        lo = min(lo, ks);
-        hi = max(hi, ks);
-      }
-    }
-    ksr[tid] = lo | (hi << 8);
-  }
-  __syncthreads();
 
   // DFT operand: slot x16 of tile tt (tt = 0: Re X[0..15]; tt = 1: Re X[16], Im X[1..15]),
   // k-slots = tokens.  Entries are 64 * (w/2) * {cos, -sin}(2 pi k t / 32) with
@@ -114,52 +87,42 @@ __global__ __launch_bounds__(256) void k_encode_mfma_kernel(const u32x4* __restr
   const int bits_h = 6 * n_a;                        // half-word offsets inside the record
   const int meta_h = 6 * n_a + 2 * n_n;
   const int nblk = n_n >> 3;
+  // my 8 token slots start at row 4*kb (slots 0-3) and 16 + 4*kb (slots 4-7)
+  const uint8_t* tcol = reinterpret_cast<const uint8_t*>(&tile4[wave][0]) + 4 * kb * ENC_ROW;
 
   const int g_begin = blockIdx.x * ENC_GPB;
   const int g_end = min(ng, g_begin + ENC_GPB);
   const u32x4* head = K + hd * (long long)T * 16;
 
-  u32x4 Apre[2][4];
+  // coalesced tile load: lane reads 16 bytes of row (lane >> 4) + 4 i, i = 0..7
+  u32x4 pre[8];
   auto prefetch = [&](int g) {
-    const u32x4* src = head + (long long)g * G * 16;
+    const u32x4* src = head + (long long)g * G * 16 + lane;
 #pragma unroll
-    for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-      for (int ks = 0; ks < 4; ++ks)
-        Apre[mt][ks] = __builtin_nontemporal_load(src + (16 * mt + x16) * 16 + 4 * ks + kb);
+    for (int i = 0; i < 8; ++i) pre[i] = __builtin_nontemporal_load(src + 64 * i);
   };
   int g = g_begin + wave;
   if (g < g_end) prefetch(g);
 
   for (; g < g_end; g += 4) {
-    Op A[2][4];
+    {
+      uint8_t* wdst = reinterpret_cast<uint8_t*>(&tile4[wave][0]) + kb * ENC_ROW + x16 * 16;
 #pragma unroll
-    for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-      for (int ks = 0; ks < 4; ++ks) A[mt][ks].q = Apre[mt][ks];
+      for (int i = 0; i < 8; ++i) *reinterpret_cast<u32x4*>(wdst + 4 * i * ENC_ROW) = pre[i];
+    }
     if (g + 4 < g_end) prefetch(g + 4);
 
 #pragma unroll
-    for (int j = 0; j < NT; ++j) {
-      const int kr = __builtin_amdgcn_readfirstlane(ksr[j]);
-      const int klo = kr & 255, khi = kr >> 8;
-      // ---- gather + transpose: T[mt] = tokens (rows) x 16 permuted channels (columns)
-      f4 T0 = f4{0.f, 0.f, 0.f, 0.f}, T1 = f4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int ks = 0; ks < 4; ++ks) {
-        if (ks >= klo && ks <= khi) {
-          Op S;
-          S.q = sel[j][ks][lane];
-          T0 = mma(A[0][ks], S, T0);
-          T1 = mma(A[1][ks], S, T1);
-        }
-      }
-      // my column's channel at my 8 token slots, as an operand (exact fp16 values)
+    for (int j = 0; j < ENC_MAXT; ++j) {
+      if (j >= NT) break;
+      // my column's channel at my 8 token slots: 16-bit LDS loads into register halves
       Op X;
-      X.p[0] = pk_f16(T0[0], T0[1]);
-      X.p[1] = pk_f16(T0[2], T0[3]);
-      X.p[2] = pk_f16(T1[0], T1[1]);
-      X.p[3] = pk_f16(T1[2], T1[3]);
+      const uint8_t* cp = tcol + chofs[j];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int row = (i < 4) ? i : 12 + i;          // relative to row 4*kb
+        X.v[i] = *reinterpret_cast<const _Float16*>(cp + row * ENC_ROW);
+      }
 
       if (j < NTa) {
         // ---------------- Eq. 4, 2 bits: z = min, s = (max - min) / 3 over the 32 tokens
@@ -180,7 +143,6 @@ __global__ __launch_bounds__(256) void k_encode_mfma_kernel(const u32x4* __restr
           lo_f = __uint_as_float(w[0]);
           nh_f = __uint_as_float(w[1]);
         }
-        const _Float16 lo = (_Float16)lo_f;
         const float mnf = lo_f, rng = -nh_f - lo_f;
         const float inv = rng > 0.0f ? 3.0f / rng : 0.0f;
         uint32_t w0 = 0, w1 = 0;
@@ -194,9 +156,10 @@ __global__ __launch_bounds__(256) void k_encode_mfma_kernel(const u32x4* __restr
         // 4 channels of a quad (adjacent lanes) share a byte: channel r in bits 2r, 2r+1
         w0 <<= 2 * (x16 & 3);
         w1 <<= 2 * (x16 & 3);
+        const int ja = 16 * j + x16;                 // anomalous index of my column
+        if (ja >= n_a) { w0 = 0; w1 = 0; }
         w0 |= __shfl_xor(w0, 1, 64);  w1 |= __shfl_xor(w1, 1, 64);
         w0 |= __shfl_xor(w0, 2, 64);  w1 |= __shfl_xor(w1, 2, 64);
-        const int ja = 16 * j + x16;                 // anomalous index of my column
         if (ja < n_a) {
           const int quad = ja >> 2;
           if ((x16 & 3) == 0) {
@@ -208,14 +171,14 @@ __global__ __launch_bounds__(256) void k_encode_mfma_kernel(const u32x4* __restr
           }
           if (kb == 0) {
             reinterpret_cast<_Float16*>(rec16)[4 * n_a + ja] = (_Float16)(rng / 3.0f);
-            reinterpret_cast<_Float16*>(rec16)[5 * n_a + ja] = lo;
+            reinterpret_cast<_Float16*>(rec16)[5 * n_a + ja] = (_Float16)lo_f;
           }
         }
       } else {
         // ---------------- Eq. 5: 32-point DFT along tokens, sign bits and mean-|.| scales
         const int jn = j - NTa;
-        // [channel][slot]: my column = slot x16, my rows = channels 4kb + i of the tile
         const f4 zero = f4{0.f, 0.f, 0.f, 0.f};
+        // [channel][slot]: my column = slot x16, my rows = channels 4kb + i of the tile
         f4 sRe = mma(X, F[0][0], zero), sIm = mma(X, F[1][0], zero);
         sRe = mma(X, F[0][1], sRe);  sIm = mma(X, F[1][1], sIm);
         sRe = mma(X, F[0][2], sRe);  sIm = mma(X, F[1][2], sIm);

@@ -126,28 +126,25 @@ __global__ __launch_bounds__(256) void v_sel_level_kernel(const float* __restric
   __syncthreads();
   if (!s_last) return;
   __threadfence();
-  // last workgroup of this sequence: find the bin that holds the remaining-th largest key
+  // last workgroup of this sequence: find the bin that holds the remaining-th
+  // largest key.  Thread t owns the PER bins of group 255 - t, so an exclusive
+  // scan over threads gives the count of keys in all higher bins.
   constexpr int PER = NB / 256;
+  const int grp = 255 - tid;
+  int c[PER];
   int mine = 0;
 #pragma unroll
-  for (int i = 0; i < PER; ++i) mine += ld_dev(&gh[tid * PER + i]);
-  cum[tid] = mine;
-  __syncthreads();
-  if (tid == 0) {
-    int rem = ld_dev(&w.st[b * 4 + 1]);
-    int th = 255;
-    for (; th > 0; --th) {
-      if (cum[th] >= rem) break;
-      rem -= cum[th];
-    }
-    int bin = th * PER + PER - 1;
-    for (; bin > th * PER; --bin) {
-      const int c = ld_dev(&gh[bin]);
-      if (c >= rem) break;
-      rem -= c;
-    }
-    w.st[b * 4 + 0] = (int)(prefix | ((uint32_t)bin << SHIFT));
-    w.st[b * 4 + 1] = rem;
+  for (int i = 0; i < PER; ++i) { c[i] = ld_dev(&gh[grp * PER + i]); mine += c[i]; }
+  const int rem = ld_dev(&w.st[b * 4 + 1]);
+  int tot;
+  const int above = block_exscan_256(mine, cum, &tot);
+  if (above < rem && rem <= above + mine) {          // exactly one thread
+    int r = rem - above, i = PER - 1;
+#pragma unroll
+    for (int k = PER - 1; k > 0; --k)
+      if (i == k && c[k] < r) { r -= c[k]; i = k - 1; }
+    w.st[b * 4 + 0] = (int)(prefix | ((uint32_t)(grp * PER + i) << SHIFT));
+    w.st[b * 4 + 1] = r;
   }
 }
 
@@ -201,14 +198,21 @@ __global__ __launch_bounds__(256) void v_sel_count_kernel(const float* __restric
   __syncthreads();
   if (!s_last) return;
   __threadfence();
-  if (tid == 0) {
-    int as = 0, ae = 0;
-    for (int i = 0; i < w.nslice; ++i) {
-      w.pre[((size_t)b * w.nslice + i) * 2 + 0] = as;
-      w.pre[((size_t)b * w.nslice + i) * 2 + 1] = ae;
-      as += ld_dev(&w.cnt[((size_t)b * w.nslice + i) * 2 + 0]);
-      ae += ld_dev(&w.cnt[((size_t)b * w.nslice + i) * 2 + 1]);
+  // exclusive prefixes over the slices, 256 slices at a time
+  int carry_s = 0, carry_e = 0;
+  for (int i0 = 0; i0 < w.nslice; i0 += 256) {
+    const int i = i0 + tid;
+    const int cs = i < w.nslice ? ld_dev(&w.cnt[((size_t)b * w.nslice + i) * 2 + 0]) : 0;
+    const int ce = i < w.nslice ? ld_dev(&w.cnt[((size_t)b * w.nslice + i) * 2 + 1]) : 0;
+    int ts, te;
+    const int ps = block_exscan_256(cs, sw, &ts);
+    const int pe = block_exscan_256(ce, sw, &te);
+    if (i < w.nslice) {
+      w.pre[((size_t)b * w.nslice + i) * 2 + 0] = carry_s + ps;
+      w.pre[((size_t)b * w.nslice + i) * 2 + 1] = carry_e + pe;
     }
+    carry_s += ts;
+    carry_e += te;
   }
 }
 

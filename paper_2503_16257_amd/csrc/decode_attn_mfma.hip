@@ -1,43 +1,51 @@
 // MFMA decode attention over the packed cache (Eq. 3; Alg. 1, Decoding).
 //
-// One wave walks PAIRS of 32-token groups.  All contractions run on
+// One wave walks PAIRS of 32-token groups; the 16 "columns" of the score tiles
+// are (group parity, query head <= 8).  All contractions run on
 // v_mfma_f32_16x16x32_f16 with operands that are exact in fp16 and fp32
 // accumulation:
 //   * normal key channels (Eq. 5): rows = DFT coefficient slot, K = channels,
 //     operand value -(+-s) built from one sign bit and the stored fp16 scale;
-//     columns = (group parity, query head) with -q/16 as the other operand.
-//     The result is already laid out as the B operand of the next product,
+//     columns carry -q/16.  The result tile is already laid out as the B operand
+//     of the next product,
 //   * a 32-point inverse real DFT as a product with a constant matrix (split
-//     into fp16 hi + lo parts, as is Y) giving scores[token][head],
+//     into fp16 hi + lo parts, as is Y) giving scores[token][column],
 //   * anomalous key channels (Eq. 4): code*s + z = (z + 1.5 s) + s0 (s/2) + s1 s
-//     with s0, s1 = +-1 taken from the two code bits, rows = tokens,
-//   * P V: rows = channels, K = tokens, operand +-s/2 * 2 or 0 from the trits.
+//     with s0, s1 = +-1 taken from the two code bits, rows = tokens; the column
+//     operand is masked by parity so both groups add into the same score tile,
+//   * P V: rows = columns of the score tile (probabilities are reused in place
+//     as the A operand), K = tokens, columns = channels with operand +-2 / 0 from
+//     the trits; the per-channel scale of Eq. 6 multiplies the fp32 result.
 // Softmax is online in the exp2 domain with a lazily raised running maximum
 // shared by the two parities of a head.  Protected (fp16) value rows are added
 // on the VALU from the probabilities staged in LDS.
-//
-// MFMA register layout used throughout (lane = 16*kb + x, x = lane & 15):
-//   A operand: row x,    k = 8*kb .. 8*kb+7       B operand: column x, same k
-//   C/D      : column x, rows 4*kb .. 4*kb+3
 #include "decode_attn.h"
 
 namespace vidkv {
 
-// packed fp16 multiply of a by the low / high half of s broadcast to both lanes
-__device__ __forceinline__ uint32_t pk_mul_bcast_lo(uint32_t a, uint32_t s) {
-  uint32_t d;
-  asm("v_pk_mul_f16 %0, %1, %2 op_sel_hi:[1,0]" : "=v"(d) : "v"(a), "v"(s));
-  return d;
-}
-__device__ __forceinline__ uint32_t pk_mul_bcast_hi(uint32_t a, uint32_t s) {
-  uint32_t d;
-  asm("v_pk_mul_f16 %0, %1, %2 op_sel:[0,1] op_sel_hi:[1,1]" : "=v"(d) : "v"(a), "v"(s));
-  return d;
-}
-
 constexpr int KCH_MAX = 1536 / 16;     // 16-byte chunks of the largest key record
 
-template <int NA8>
+__device__ __forceinline__ uint32_t pkrtz(float a, float b) {
+  return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(a, b));
+}
+__device__ __forceinline__ float swap_sum32(float v) {       // v(lane) + v(lane ^ 32)
+  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+__device__ __forceinline__ float swap_sum16(float v) {       // v(lane) + v(lane ^ 16)
+  auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+__device__ __forceinline__ float swap_max32(float v) {
+  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float swap_max16(float v) {
+  auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
+template <int NA8, bool HAS_SAL>
 __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a) {
   constexpr int NA = 8 * NA8, NN = D - NA;
   constexpr int NB = NN / 8;                 // normal 8-channel blocks
@@ -55,16 +63,17 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a) {
   const int hcol = x16 & 7, par = x16 >> 3;          // column role: (parity, head)
   const int R = a.rep;
   const long long hd = ((long long)a.layer * a.B + b) * a.H + kvh;
+  const f4 zero = f4{0.f, 0.f, 0.f, 0.f};
 
   __shared__ u32x4 kl4[4][2][KCH_MAX];       // per wave: key records of the two groups
   __shared__ float pl[4][32][16];            // per wave: probabilities [token][column]
-  __shared__ float al8[4][8];                // per wave: rescale factors per head
+  __shared__ float al16[4][16];              // per wave: rescale factors per column
   __shared__ float ow[4][8][D];              // per wave partial outputs
   __shared__ float mw[4][8], lw[4][8];
-
-  // ---------------- constant operands (q and the channel permutation via LDS)
   __shared__ _Float16 qs[8][D];
   __shared__ uint8_t perm_s[D];
+
+  // ---------------- constant operands (q and the channel permutation via LDS)
   {
     const uint32_t* qsrc = reinterpret_cast<const uint32_t*>(a.q + ((long long)b * a.Hq + kvh * R) * D);
     for (int i = tid; i < R * (D / 2); i += 256) reinterpret_cast<uint32_t*>(&qs[0][0])[i] = qsrc[i];
@@ -74,27 +83,28 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a) {
   __syncthreads();
   const bool hv = hcol < R;
   const _Float16* qrow = &qs[hv ? hcol : 0][0];
-  const uint8_t* perm = perm_s;
-  Op Bn[U > 0 ? U : 1];
+  Op Bn[U > 0 ? U : 1];                      // normal channels: -q/16 at channels 8 (4u+kb) + e
 #pragma unroll
   for (int u = 0; u < U; ++u) {
     const int blk = 4 * u + kb;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
       float v = 0.0f;
-      if (hv && blk < NB) v = -(float)qrow[perm[NA + 8 * blk + e]] * 0.0625f;
+      if (hv && blk < NB) v = -(float)qrow[perm_s[NA + 8 * blk + e]] * 0.0625f;
       Bn[u].v[e] = (_Float16)v;
     }
   }
-  Op Ba[UA > 0 ? UA : 1];
+  Op Ba[2][UA > 0 ? UA : 1];                 // anomalous: (-q, -q) per channel, only in my parity
 #pragma unroll
   for (int ua = 0; ua < UA; ++ua) {
     const int quad = 4 * ua + kb;
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
       float v = 0.0f;
-      if (hv && quad < NQ) v = -(float)qrow[perm[4 * quad + r]];
-      Ba[ua].p[r] = h2{(_Float16)v, (_Float16)v};
+      if (hv && quad < NQ) v = -(float)qrow[perm_s[4 * quad + r]];
+      const uint32_t pr = h2_bits(h2{(_Float16)v, (_Float16)v});
+      Ba[0][ua].u[r] = par ? 0u : pr;
+      Ba[1][ua].u[r] = par ? pr : 0u;
     }
   }
   // 16 * (inverse real DFT matrix): row t, k-slot (kb, i): i < 4 -> Re X[4kb+i],
@@ -116,13 +126,15 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a) {
   }
 
   // ---------------- running state
+  // o[m][i]: row 4kb+i = (parity, head) column of the score tile, channel 16 m + x16;
+  // holds 2 * sum p * code * s of the quantized tokens (halved at the end).
   f4 o[8];
 #pragma unroll
-  for (int m = 0; m < 8; ++m) o[m] = f4{0.f, 0.f, 0.f, 0.f};
-  float osal[8][2];
+  for (int m = 0; m < 8; ++m) o[m] = zero;
+  float osal[8][2];                          // protected rows: head h, channels 2 lane, 2 lane + 1
 #pragma unroll
   for (int h = 0; h < 8; ++h) { osal[h][0] = 0.f; osal[h][1] = 0.f; }
-  float m_run = -INFINITY, l_run = 0.0f;
+  float m_run = -INFINITY, l_run = 0.0f;     // of my column (shared by both parities of a head)
 
   const int npairs = (a.ng + 1) >> 1;
   const int p_begin = split * a.gps;
@@ -131,8 +143,9 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a) {
   const uint8_t* krec_base = a.krec + hd * a.ng * (long long)KREC;
   const uint8_t* vrec_base = a.vrec + hd * a.ng * (long long)VREC;
 
-  // prefetch registers: key record chunks, value words and scales of both groups
-  u32x4 kpre[2][2], vwpre[2], vspre[2];
+  // prefetch registers: key record chunks and value words of both groups, value
+  // scales of the group whose rows this lane owns in the PV tile (parity kb >> 1)
+  u32x4 kpre[2][2], vwpre[2], vspre;
   auto prefetch = [&](int p) {
 #pragma unroll
     for (int grp = 0; grp < 2; ++grp) {
@@ -142,18 +155,18 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a) {
       kpre[grp][1] = ks[lane + 64 < KCH ? lane + 64 : 0];
       const u32x4* vs = reinterpret_cast<const u32x4*>(vrec_base + (long long)g * VREC);
       vwpre[grp] = vs[lane];
-      vspre[grp] = vs[64 + x16];
     }
+    const int gs = min(2 * p + (kb >> 1), a.ng - 1);
+    vspre = reinterpret_cast<const u32x4*>(vrec_base + (long long)gs * VREC)[64 + x16];
   };
   // Protected rows are fetched one pair ahead, their masks two pairs ahead.
   // The rows of one pair are consecutive in ROWS (rank grows with the token).
   constexpr int NROW = 8;
   uint32_t rowcur[NROW], rownext[NROW];
   uint32_t sm0c = 0, sm1c = 0, rkc = 0, sm0n = 0, sm1n = 0, rkn = 0;
-  const bool has_sal = a.n_s > 0;
   auto load_masks = [&](int pp, uint32_t& s0, uint32_t& s1, uint32_t& rk) {
     s0 = s1 = rk = 0;
-    if (has_sal && pp < p_end) {
+    if (HAS_SAL && pp < p_end) {
       const size_t gi = (size_t)b * a.ng + 2 * pp;
       s0 = a.vmask[gi];
       rk = a.vrank[gi];
@@ -169,7 +182,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a) {
   };
   int p = p_begin + wave;
   if (p < p_end) prefetch(p);
-  if (has_sal) {
+  if (HAS_SAL) {
     load_masks(p, sm0c, sm1c, rkc);
     load_masks(p + 4, sm0n, sm1n, rkn);
     if (sm0c | sm1c) issue_rows(sm0c, sm1c, rkc, rowcur);
@@ -178,29 +191,29 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a) {
   for (; p < p_end; p += 4) {
     const bool v1ok = (2 * p + 1) < a.ng;
     // ---- commit the prefetched data, start the next prefetch
-    u32x4 vw[2], vs[2];
+    u32x4 vw[2];
+    Op sv;
 #pragma unroll
     for (int grp = 0; grp < 2; ++grp) {
       if (lane < KCH) kl4[wave][grp][lane] = kpre[grp][0];
       if (lane + 64 < KCH) kl4[wave][grp][lane + 64] = kpre[grp][1];
       vw[grp] = vwpre[grp];
-      vs[grp] = vspre[grp];
     }
+    sv.q = vspre;
     if (p + 4 < p_end) prefetch(p + 4);
     uint32_t sm0f = 0, sm1f = 0, rkf = 0;        // masks of the pair after the next one
-    if (has_sal) {
+    if (HAS_SAL) {
       if (sm0n | sm1n) issue_rows(sm0n, sm1n, rkn, rownext);
       load_masks(p + 8, sm0f, sm1f, rkf);
     }
 
+    f4 S[2] = {zero, zero};                      // scores[token][column]
     // ---- normal channels: Y[slot][col] per group, K = channels
-    f4 accRe[2], accIm[2];
     if (U > 0) {
+      f4 accRe[2], accIm[2];
 #pragma unroll
       for (int grp = 0; grp < 2; ++grp) {
         const uint8_t* rec = reinterpret_cast<const uint8_t*>(&kl4[wave][grp][0]);
-        accRe[grp] = f4{0.f, 0.f, 0.f, 0.f};
-        accIm[grp] = f4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int u = 0; u < U; ++u) {
           const int blk = min(4 * u + kb, NB - 1);
@@ -211,51 +224,52 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a) {
           sim.q = *reinterpret_cast<const u32x4*>(rec + OFF_META + (blk * 2 + (x16 ? 1 : 0)) * 16);
 #pragma unroll
           for (int r = 0; r < 4; ++r) A.u[r] = ((xx << (15 - 2 * r)) & 0x80008000u) | sre.u[r];
-          accRe[grp] = mma(A, Bn[u], accRe[grp]);
+          accRe[grp] = mma(A, Bn[u], u == 0 ? zero : accRe[grp]);
 #pragma unroll
           for (int r = 0; r < 4; ++r) A.u[r] = ((xx << (7 - 2 * r)) & 0x80008000u) | sim.u[r];
-          accIm[grp] = mma(A, Bn[u], accIm[grp]);
+          accIm[grp] = mma(A, Bn[u], u == 0 ? zero : accIm[grp]);
         }
       }
-    }
-    f4 S[2] = {f4{0.f, 0.f, 0.f, 0.f}, f4{0.f, 0.f, 0.f, 0.f}};
-    if (U > 0) {
       // my column belongs to group `par`; split Y/16 into fp16 hi + lo
       Op Yh, Yl;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const float yr = par ? accRe[1][i] : accRe[0][i];
-        const float yi = par ? accIm[1][i] : accIm[0][i];
-        const _Float16 hr = (_Float16)yr, hi = (_Float16)yi;
-        Yh.v[i] = hr;
-        Yh.v[4 + i] = hi;
-        Yl.v[i] = (_Float16)(yr - (float)hr);
-        Yl.v[4 + i] = (_Float16)(yi - (float)hi);
+      for (int i = 0; i < 4; i += 2) {
+        const float r0 = par ? accRe[1][i] : accRe[0][i], r1 = par ? accRe[1][i + 1] : accRe[0][i + 1];
+        const float i0 = par ? accIm[1][i] : accIm[0][i], i1 = par ? accIm[1][i + 1] : accIm[0][i + 1];
+        Yh.u[i / 2] = pkrtz(r0, r1);
+        Yh.u[2 + i / 2] = pkrtz(i0, i1);
+        Yl.u[i / 2] = pkrtz(r0 - (float)Yh.v[i], r1 - (float)Yh.v[i + 1]);
+        Yl.u[2 + i / 2] = pkrtz(i0 - (float)Yh.v[4 + i], i1 - (float)Yh.v[4 + i + 1]);
       }
 #pragma unroll
       for (int mt = 0; mt < 2; ++mt) {
-        S[mt] = mma(Wh[mt], Yh, S[mt]);
+        S[mt] = mma(Wh[mt], Yh, zero);
         S[mt] = mma(Wl[mt], Yh, S[mt]);
         S[mt] = mma(Wh[mt], Yl, S[mt]);
       }
     }
-    // ---- anomalous channels: rows = tokens, K = (channel, bit plane)
+    // ---- anomalous channels: rows = tokens, K = (channel, bit plane); the column
+    // operand is zero outside my parity, so both groups add into S directly
     float cst = 0.0f;
     if (UA > 0) {
-      f4 accA[2][2], accC[2];
+      f4 accC = zero;
 #pragma unroll
       for (int grp = 0; grp < 2; ++grp) {
         const uint8_t* rec = reinterpret_cast<const uint8_t*>(&kl4[wave][grp][0]);
-        accA[grp][0] = accA[grp][1] = accC[grp] = f4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int ua = 0; ua < UA; ++ua) {
           const int quad = min(4 * ua + kb, NQ - 1);
-          union { uint2 u; _Float16 e[4]; } s4, z4;
-          s4.u = *reinterpret_cast<const uint2*>(rec + OFF_AS + quad * 8);
-          z4.u = *reinterpret_cast<const uint2*>(rec + OFF_AZ + quad * 8);
-          uint32_t sp[4];
+          Op s4, z4;                                             // 4 halves each (low 8 bytes used)
+          *reinterpret_cast<uint2*>(&s4) = *reinterpret_cast<const uint2*>(rec + OFF_AS + quad * 8);
+          *reinterpret_cast<uint2*>(&z4) = *reinterpret_cast<const uint2*>(rec + OFF_AZ + quad * 8);
+          uint32_t sp[4];                                        // (s/2, s) of channel r
+          Op Ac1, Ac2;
 #pragma unroll
-          for (int r = 0; r < 4; ++r) sp[r] = h2_bits(h2{s4.e[r] * (_Float16)0.5f, s4.e[r]});
+          for (int r = 0; r < 4; ++r) {
+            sp[r] = h2_bits(h2{s4.v[r] * (_Float16)0.5f, s4.v[r]});
+            Ac1.p[r] = h2{z4.v[r], s4.v[r]};                     // z + s
+            Ac2.u[r] = sp[r] & 0xFFFFu;                          // + s/2
+          }
 #pragma unroll
           for (int mt = 0; mt < 2; ++mt) {
             const uint32_t w = rec[(16 * mt + x16) * NQ + quad];
@@ -263,108 +277,115 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a) {
             Op A;
 #pragma unroll
             for (int r = 0; r < 4; ++r) A.u[r] = ((xx << (15 - 2 * r)) & 0x80008000u) | sp[r];
-            accA[grp][mt] = mma(A, Ba[ua], accA[grp][mt]);
+            S[mt] = mma(A, Ba[grp][ua], S[mt]);
           }
-          // constant part z + 1.5 s = z + s + s/2, same for every row
-#pragma unroll
-          for (int hf = 0; hf < 2; ++hf) {
-            Op Ac, Bc;
-            Ac.p[0] = h2{z4.e[2 * hf], s4.e[2 * hf]};
-            Ac.u[1] = sp[2 * hf] & 0xFFFFu;
-            Ac.p[2] = h2{z4.e[2 * hf + 1], s4.e[2 * hf + 1]};
-            Ac.u[3] = sp[2 * hf + 1] & 0xFFFFu;
-            Bc.u[0] = Ba[ua].u[2 * hf];
-            Bc.u[1] = Ba[ua].u[2 * hf];
-            Bc.u[2] = Ba[ua].u[2 * hf + 1];
-            Bc.u[3] = Ba[ua].u[2 * hf + 1];
-            accC[grp] = mma(Ac, Bc, accC[grp]);
-          }
+          accC = mma(Ac1, Ba[grp][ua], accC);                    // rows all equal
+          accC = mma(Ac2, Ba[grp][ua], accC);
         }
       }
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        S[0][i] += par ? accA[1][0][i] : accA[0][0][i];
-        S[1][i] += par ? accA[1][1][i] : accA[0][1][i];
-      }
-      cst = par ? accC[1][0] : accC[0][0];      // = -(sum q (z + 1.5 s))
+      cst = accC[0];                                             // = -(sum q (z + 1.5 s))
     }
-    // ---- scores of my column: token slot i (i < 4: token 4kb+i, else 16+4kb+i-4)
-    float sc[8];
+    // ---- t = score - running maximum, in the exp2 domain, for my column at token
+    // slot i (i < 4: token 4kb+i, else 16+4kb+i-4)
+    float c1 = -cst * a.scale2 - m_run;
+    float t[8];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      sc[i] = (S[0][i] - cst) * a.scale2;
-      sc[4 + i] = (S[1][i] - cst) * a.scale2;
+      t[i] = fmaf(S[0][i], a.scale2, c1);
+      t[4 + i] = fmaf(S[1][i], a.scale2, c1);
     }
     if (par && !v1ok) {
 #pragma unroll
-      for (int i = 0; i < 8; ++i) sc[i] = -INFINITY;
+      for (int i = 0; i < 8; ++i) t[i] = -INFINITY;
     }
-    // ---- online softmax.  The running maximum m_run is shared by the 4 k-blocks
-    // and the 2 parities of a head and is raised lazily: only when some score
-    // exceeds it by more than 8 (p stays below 2^8), which needs no cross-lane
-    // traffic in the common case.
-    float mx = sc[0];
+    // ---- online softmax.  The running maximum is raised lazily: only when some
+    // score exceeds it by more than 8 (p stays below 2^8), which needs no
+    // cross-lane traffic in the common case.
+    float mx = t[0];
 #pragma unroll
-    for (int i = 1; i < 8; ++i) mx = fmaxf(mx, sc[i]);
-    if (__any(mx > m_run + 8.0f)) {
-      mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      mx = fmaxf(mx, __shfl_xor(mx, 8, 64));
-      const float m_new = fmaxf(m_run, mx);
+    for (int i = 1; i < 8; ++i) mx = fmaxf(mx, t[i]);
+    if (__any(mx > 8.0f)) {
+      // true scores again; maximum over the 4 k-blocks and the 2 parities of the head
+      float smax = (m_run == -INFINITY) ? -INFINITY : mx + m_run;
+      if (m_run == -INFINITY) {
+        const float c0 = -cst * a.scale2;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          t[i] = fmaf(S[0][i], a.scale2, c0);
+          t[4 + i] = fmaf(S[1][i], a.scale2, c0);
+        }
+        if (par && !v1ok) {
+#pragma unroll
+          for (int i = 0; i < 8; ++i) t[i] = -INFINITY;
+        }
+        smax = t[0];
+#pragma unroll
+        for (int i = 1; i < 8; ++i) smax = fmaxf(smax, t[i]);
+      }
+      smax = swap_max32(smax);
+      smax = swap_max16(smax);
+      smax = fmaxf(smax, __shfl_xor(smax, 8, 64));
+      const float m_new = fmaxf(m_run, smax);
       const float al = (m_run == -INFINITY) ? 0.0f : __builtin_amdgcn_exp2f(m_run - m_new);
+      const float shift = (m_run == -INFINITY) ? -m_new : m_run - m_new;
 #pragma unroll
-      for (int m = 0; m < 8; ++m) o[m] *= al;
+      for (int i = 0; i < 8; ++i) t[i] += shift;
       l_run *= al;
       m_run = m_new;
-      if (has_sal) {
-        if (lane < 8) al8[wave][lane] = al;
-        float ah[8];
+      // the PV accumulators are laid out by score-tile column as ROW 4kb + i
+      if (kb == 0) al16[wave][x16] = al;
+      float ar[4];
 #pragma unroll
-        for (int h = 0; h < 8; ++h) ah[h] = al8[wave][h];
+      for (int i = 0; i < 4; ++i) ar[i] = al16[wave][4 * kb + i];
 #pragma unroll
-        for (int h = 0; h < 8; ++h) { osal[h][0] *= ah[h]; osal[h][1] *= ah[h]; }
+      for (int m = 0; m < 8; ++m)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) o[m][i] *= ar[i];
+      if (HAS_SAL) {
+#pragma unroll
+        for (int h = 0; h < 8; ++h) {
+          const float ah = al16[wave][h];
+          osal[h][0] *= ah;
+          osal[h][1] *= ah;
+        }
       }
     }
     float pr[8];
-    Op Pp;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      pr[i] = __builtin_amdgcn_exp2f(sc[i] - m_run);
+      pr[i] = __builtin_amdgcn_exp2f(t[i]);
       l_run += pr[i];
-      Pp.v[i] = (_Float16)pr[i];
     }
-    Op Bp[2];
+    // probabilities as the A operand of P V (row = my column), zero outside the group
+    Op Ap[2];
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-      Bp[0].u[r] = par ? 0u : Pp.u[r];
-      Bp[1].u[r] = par ? Pp.u[r] : 0u;
+      const uint32_t pp = pkrtz(pr[2 * r], pr[2 * r + 1]);
+      Ap[0].u[r] = par ? 0u : pp;
+      Ap[1].u[r] = par ? pp : 0u;
     }
-    // ---- P V: rows = channels 16 m + x16, K = token slots
+    // ---- P V: C[column][channel 16 m + x16] = sum_t p * (2 code), then o += s * C
 #pragma unroll
-    for (int grp = 0; grp < 2; ++grp) {
-      Op hs;
+    for (int m = 0; m < 8; ++m) {
+      f4 C = zero;
 #pragma unroll
-      for (int r = 0; r < 4; ++r) hs.p[r] = bits_h2(vs[grp][r]) * h2{(_Float16)0.5f, (_Float16)0.5f};
-#pragma unroll
-      for (int m = 0; m < 8; ++m) {
+      for (int grp = 0; grp < 2; ++grp) {
         const uint32_t w = vw[grp][m >> 1];
-        Op A;
+        Op Bv;
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const uint32_t t2 = (w << ((m & 1) ? (6 - 2 * r) : (14 - 2 * r))) & 0xC000C000u;   // +-2 or 0
-          A.u[r] = (m & 1) ? pk_mul_bcast_hi(t2, hs.u[m >> 1]) : pk_mul_bcast_lo(t2, hs.u[m >> 1]);
-        }
-        o[m] = mma(A, Bp[grp], o[m]);
+        for (int r = 0; r < 4; ++r)
+          Bv.u[r] = (w << ((m & 1) ? (6 - 2 * r) : (14 - 2 * r))) & 0xC000C000u;   // +-2 or 0
+        C = mma(Ap[grp], Bv, C);
       }
+      const float sc = (float)sv.v[m];           // Eq. 6 scale of channel 16 m + x16, my rows' group
+#pragma unroll
+      for (int i = 0; i < 4; ++i) o[m][i] = fmaf(sc, C[i], o[m][i]);
     }
     // ---- protected tokens: fp16 rows (prefetched) weighted by the probabilities
-    if (has_sal) {
+    if (HAS_SAL) {
       if (sm0c | sm1c) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-          const int t = (i < 4) ? 4 * kb + i : 16 + 4 * kb + (i - 4);
-          pl[wave][t][x16] = pr[i];
-        }
+        for (int i = 0; i < 8; ++i) pl[wave][slot_token(kb, i)][x16] = pr[i];
         unsigned long long sm = (unsigned long long)sm0c | ((unsigned long long)sm1c << 32);
         auto add_row = [&](uint32_t bits) {
           const int t64 = __ffsll((long long)sm) - 1;      // bit t of parity t64 >> 5
@@ -395,22 +416,24 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a) {
     }
   }
 
-  // ---------------- per-wave reduction: 4 k-blocks and 2 parities of each head
-  l_run += __shfl_xor(l_run, 16, 64);
-  l_run += __shfl_xor(l_run, 32, 64);
+  // ---------------- per-wave reduction
+  // l: 4 k-blocks and 2 parities of each head
+  l_run = swap_sum32(l_run);
+  l_run = swap_sum16(l_run);
   l_run += __shfl_xor(l_run, 8, 64);
+  // o: rows 4kb+i; parity 1 rows live 32 lanes away from their parity 0 partners
 #pragma unroll
   for (int m = 0; m < 8; ++m)
 #pragma unroll
-    for (int i = 0; i < 4; ++i) o[m][i] += __shfl_xor(o[m][i], 8, 64);
-  if (par == 0) {
+    for (int i = 0; i < 4; ++i) o[m][i] = swap_sum32(o[m][i]);
+  if (kb < 2) {
 #pragma unroll
     for (int m = 0; m < 8; ++m)
 #pragma unroll
-      for (int i = 0; i < 4; ++i) ow[wave][hcol][16 * m + 4 * kb + i] = o[m][i];
-    if (kb == 0) { mw[wave][hcol] = m_run; lw[wave][hcol] = l_run; }
+      for (int i = 0; i < 4; ++i) ow[wave][4 * kb + i][16 * m + x16] = 0.5f * o[m][i];
   }
-  if (a.n_s > 0) {
+  if (kb == 0 && par == 0) { mw[wave][hcol] = m_run; lw[wave][hcol] = l_run; }
+  if (HAS_SAL) {
     // same wave, LDS operations complete in order: add the fp16-row part
 #pragma unroll
     for (int h = 0; h < 8; ++h) {
@@ -449,14 +472,20 @@ bool attn_mfma_supported(int n_a) {
   }
 }
 
+template <int NA8>
+static void launch_one(const AttnArgs& a, dim3 grid, hipStream_t st) {
+  if (a.n_s > 0) hipLaunchKernelGGL((attn_mfma_kernel<NA8, true>), grid, dim3(256), 0, st, a);
+  else           hipLaunchKernelGGL((attn_mfma_kernel<NA8, false>), grid, dim3(256), 0, st, a);
+}
+
 void launch_attn_mfma(const AttnArgs& a, dim3 grid, hipStream_t st) {
   switch (a.n_a) {
-    case 0:   hipLaunchKernelGGL(attn_mfma_kernel<0>,  grid, dim3(256), 0, st, a); break;
-    case 8:   hipLaunchKernelGGL(attn_mfma_kernel<1>,  grid, dim3(256), 0, st, a); break;
-    case 16:  hipLaunchKernelGGL(attn_mfma_kernel<2>,  grid, dim3(256), 0, st, a); break;
-    case 32:  hipLaunchKernelGGL(attn_mfma_kernel<4>,  grid, dim3(256), 0, st, a); break;
-    case 64:  hipLaunchKernelGGL(attn_mfma_kernel<8>,  grid, dim3(256), 0, st, a); break;
-    case 128: hipLaunchKernelGGL(attn_mfma_kernel<16>, grid, dim3(256), 0, st, a); break;
+    case 0:   launch_one<0>(a, grid, st); break;
+    case 8:   launch_one<1>(a, grid, st); break;
+    case 16:  launch_one<2>(a, grid, st); break;
+    case 32:  launch_one<4>(a, grid, st); break;
+    case 64:  launch_one<8>(a, grid, st); break;
+    case 128: launch_one<16>(a, grid, st); break;
     default: break;
   }
 }

@@ -22,7 +22,6 @@
 
 namespace vidkv {
 
-constexpr int ENC_GPB = 16;          // groups per workgroup (4 per wave)
 constexpr int ENC_MAXT = 9;          // channel tiles of 16: at most 1 + 8
 constexpr int ENC_ROW = 272;         // LDS bytes per token row (256 + 16 of padding)
 
@@ -31,7 +30,7 @@ constexpr int ENC_ROW = 272;         // LDS bytes per token row (256 + 16 of pad
 template <int NA8T>
 __global__ __launch_bounds__(256) void k_encode_mfma_kernel(const u32x4* __restrict__ K,
                                                             const uint8_t* __restrict__ perm_g,
-                                                            int T, int ng, int n_a_rt, int krec,
+                                                            int T, int ng, int n_a_rt, int krec, int gpb,
                                                             uint8_t* __restrict__ rec_out) {
   const int n_a = NA8T >= 0 ? 8 * NA8T : n_a_rt;
   const long long hd = blockIdx.y;
@@ -90,8 +89,8 @@ __global__ __launch_bounds__(256) void k_encode_mfma_kernel(const u32x4* __restr
   // my 8 token slots start at row 4*kb (slots 0-3) and 16 + 4*kb (slots 4-7)
   const uint8_t* tcol = reinterpret_cast<const uint8_t*>(&tile4[wave][0]) + 4 * kb * ENC_ROW;
 
-  const int g_begin = blockIdx.x * ENC_GPB;
-  const int g_end = min(ng, g_begin + ENC_GPB);
+  const int g_begin = blockIdx.x * gpb;
+  const int g_end = min(ng, g_begin + gpb);
   const u32x4* head = K + hd * (long long)T * 16;
 
   // coalesced tile load: lane reads 16 bytes of row (lane >> 4) + 4 i, i = 0..7
@@ -223,12 +222,13 @@ __global__ __launch_bounds__(256) void k_encode_mfma_kernel(const u32x4* __restr
 }
 
 void launch_k_encode(const Geom& g, const void* K, uint8_t* packed, hipStream_t st) {
-  dim3 grid((g.ng + ENC_GPB - 1) / ENC_GPB, (unsigned)g.nheads);
+  const int gpb = pick_groups_per_wg(g.ng, g.nheads, 4 * device_cu_count());   // 4 workgroups per CU
+  dim3 grid((g.ng + gpb - 1) / gpb, (unsigned)g.nheads);
   const u32x4* k4 = reinterpret_cast<const u32x4*>(K);
   const uint8_t* perm = packed + g.k_perm;
   uint8_t* rec = packed + g.k_rec;
 #define VIDKV_ENC(N) \
-  hipLaunchKernelGGL(k_encode_mfma_kernel<N>, grid, dim3(256), 0, st, k4, perm, g.T, g.ng, g.n_a, g.krec, rec)
+  hipLaunchKernelGGL(k_encode_mfma_kernel<N>, grid, dim3(256), 0, st, k4, perm, g.T, g.ng, g.n_a, g.krec, gpb, rec)
   switch (g.n_a) {
     case 8:  VIDKV_ENC(1); break;
     case 16: VIDKV_ENC(2); break;

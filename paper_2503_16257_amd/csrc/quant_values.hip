@@ -272,77 +272,8 @@ __global__ __launch_bounds__(256) void v_sel_scatter_kernel(const int32_t* __res
   }
 }
 
-// ---------------------------------------------------------------------------
-// Ternary coding of one 32-token group of one head.  grid (ng, nheads), block
-// 128; thread c owns channel c.  s = mean |v| over unprotected tokens,
-// alpha = gamma * s, code = sign(v) [|v| > alpha]; protected tokens code 0 and
-// their rows go to ROWS at position RANK[g] + (order inside the group).
-// ---------------------------------------------------------------------------
-__global__ __launch_bounds__(128) void v_encode_kernel(const u32x4* __restrict__ V, int T, int ng,
-                                                       int B, int H, int n_s, float gamma,
-                                                       const uint32_t* __restrict__ mask,
-                                                       const uint32_t* __restrict__ rank,
-                                                       uint8_t* __restrict__ rec_out,
-                                                       u32x4* __restrict__ rows_out) {
-  const int g = blockIdx.x;
-  const long long hd = blockIdx.y;
-  const int tid = threadIdx.x;
-  __shared__ u32x4 tile4[32 * 16];
-  __shared__ u32x4 rec4[VREC / 16];
-  const u32x4* src = V + ((hd * T) + (long long)g * G) * 16;
-#pragma unroll
-  for (int i = 0; i < 4; ++i) tile4[tid + 128 * i] = __builtin_nontemporal_load(src + tid + 128 * i);
-  uint32_t m = 0, r0 = 0;
-  if (n_s > 0) {
-    const int b = (int)((hd / H) % B);
-    m = mask[(size_t)b * ng + g];
-    r0 = rank[(size_t)b * ng + g];
-  }
-  __syncthreads();
-  const _Float16* tile = reinterpret_cast<const _Float16*>(tile4);
-  float x[32];
-  float sum = 0.0f;
-#pragma unroll
-  for (int t = 0; t < 32; ++t) {
-    x[t] = (float)tile[t * D + tid];
-    sum += ((m >> t) & 1u) ? 0.0f : fabsf(x[t]);
-  }
-  const int n = 32 - __popc(m);
-  const float s = n > 0 ? sum / (float)n : 0.0f;
-  const float alpha = gamma * s;
-  // channel c = 16 m + r lives in word (kb, r, m >> 1); its 8 token slots fill
-  // one byte of each half-word: byte (m & 1) holds even slots, byte 2 + (m & 1) odd ones
-  uint8_t* rec8 = reinterpret_cast<uint8_t*>(rec4);
-  const int r16 = tid & 15, mt = tid >> 4;
-#pragma unroll
-  for (int kb = 0; kb < 4; ++kb) {
-    uint32_t ev = 0, od = 0;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      const int t = (j < 4) ? 4 * kb + j : 16 + 4 * kb + (j - 4);
-      const bool keep = !((m >> t) & 1u);
-      const uint32_t nz = (keep && (x[t] > alpha || x[t] < -alpha)) ? 1u : 0u;
-      const uint32_t ng_ = (keep && x[t] < -alpha) ? 1u : 0u;
-      const uint32_t f = (nz | (ng_ << 1)) << (2 * (j >> 1));
-      if (j & 1) od |= f; else ev |= f;
-    }
-    uint8_t* wbytes = rec8 + ((kb * 16 + r16) * 4 + (mt >> 1)) * 4;
-    wbytes[mt & 1] = (uint8_t)ev;
-    wbytes[2 + (mt & 1)] = (uint8_t)od;
-  }
-  reinterpret_cast<_Float16*>(rec4)[512 + r16 * 8 + mt] = (_Float16)s;
-  __syncthreads();
-  u32x4* dst = reinterpret_cast<u32x4*>(rec_out + ((hd * ng) + g) * (long long)VREC);
-  if (tid < VREC / 16) dst[tid] = rec4[tid];
-  uint32_t w = m;
-  uint32_t r = r0;
-  while (w) {
-    const int t = __ffs(w) - 1;
-    w &= w - 1;
-    if (tid < 16) rows_out[(hd * n_s + r) * 16 + tid] = tile4[t * 16 + tid];
-    ++r;
-  }
-}
+// The ternary coding pass (Eq. 6) lives in quant_values_enc.hip.
+void launch_v_encode(const Geom& g, float gamma, const void* V, uint8_t* packed, hipStream_t st);
 
 size_t values_ws_bytes(const Geom& g) {
   const int nslice = (g.T + SEL_SLICE - 1) / SEL_SLICE;
@@ -382,11 +313,7 @@ hipError_t launch_quantize_values(const Geom& g, float gamma, const void* V, con
                          idx_out, mask, rank);
     }
   }
-  dim3 gr(g.ng, (unsigned)g.nheads);
-  if (stages & 2u)
-    hipLaunchKernelGGL(v_encode_kernel, gr, dim3(128), 0, st, reinterpret_cast<const u32x4*>(V),
-                       g.T, g.ng, g.B, g.H, g.n_s, gamma, mask, rank, packed + g.v_rec,
-                       reinterpret_cast<u32x4*>(packed + g.v_rows));
+  if (stages & 2u) launch_v_encode(g, gamma, V, packed, st);
   return hipGetLastError();
 }
 

@@ -222,25 +222,39 @@ __global__ __launch_bounds__(1024) void attn_merge_kernel(const float* __restric
                                                           _Float16* __restrict__ out) {
   const int h = blockIdx.x, b = blockIdx.y;
   const int c = threadIdx.x & 127, sl = threadIdx.x >> 7;
-  __shared__ float sM[8];
   __shared__ float so[8][D];
   __shared__ float sl_[8];
+  // running maximum over all parts: one part per thread, then wave and block maxima
+  __shared__ float sW[16];
   float M = -INFINITY;
-  for (int i = sl; i < nparts; i += 8)
+  for (int i = threadIdx.x; i < nparts; i += 1024)
     M = fmaxf(M, part[(((long long)i * B + b) * Hq + h) * PART_STRIDE + D]);
-  if (c == 0) sM[sl] = M;
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) M = fmaxf(M, __shfl_xor(M, d, 64));
+  if ((threadIdx.x & 63) == 0) sW[threadIdx.x >> 6] = M;
   __syncthreads();
 #pragma unroll
-  for (int i = 0; i < 8; ++i) M = fmaxf(M, sM[i]);
+  for (int i = 0; i < 16; ++i) M = fmaxf(M, sW[i]);
+  // weighted sums, 4 parts in flight per thread
   float o = 0.0f, l = 0.0f;
-  if (M != -INFINITY) {
-    for (int i = sl; i < nparts; i += 8) {
-      const float* p = part + (((long long)i * B + b) * Hq + h) * PART_STRIDE;
-      const float mi = p[D];
-      if (mi == -INFINITY) continue;
-      const float w = exp2f(mi - M);
-      o += w * p[c];
-      l += w * p[D + 1];
+  for (int i0 = sl; i0 < nparts; i0 += 32) {
+    float mi[4], oi[4], li[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int i = i0 + 8 * u;
+      const bool ok = i < nparts;
+      const float* p = part + (((long long)(ok ? i : 0) * B + b) * Hq + h) * PART_STRIDE;
+      mi[u] = ok ? p[D] : -INFINITY;
+      oi[u] = ok ? p[c] : 0.0f;
+      li[u] = ok ? p[D + 1] : 0.0f;
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const float w = mi[u] == -INFINITY ? 0.0f : exp2f(mi[u] - M);
+      if (w != 0.0f) {                     // an empty part's sums are never looked at
+        o += w * oi[u];
+        l += w * li[u];
+      }
     }
   }
   so[sl][c] = o;

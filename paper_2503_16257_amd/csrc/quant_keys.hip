@@ -79,31 +79,46 @@ __global__ __launch_bounds__(256) void k_range_kernel(const u32x4* __restrict__ 
 // ---------------------------------------------------------------------------
 // Channel selection: R_c = float(max) - float(min); the n_a largest (ties to
 // the lower channel) are anomalous.  perm = anomalous ascending, then normal
-// ascending.  grid nheads, block 1024: 8 slices of the chunk list per channel.
+// ascending.  grid nheads, block 1024: 64 slices of the chunk list, 8 channels per thread.
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(1024) void k_select_kernel(const _Float16* __restrict__ ws,
                                                         int chunks, int n_a,
                                                         uint8_t* __restrict__ perm) {
   const long long hd = blockIdx.x;
-  const int c = threadIdx.x & 127, part = threadIdx.x >> 7;
-  const _Float16* p = ws + hd * chunks * 2 * D;
-  _Float16 lo = (_Float16)65504.0f, hi = (_Float16)-65504.0f;
-  for (int k = part; k < chunks; k += 8) {
-    const _Float16 a = p[(k * 2) * D + c], b = p[(k * 2 + 1) * D + c];
-    lo = a < lo ? a : lo;
-    hi = b > hi ? b : hi;
+  const int tid = threadIdx.x;
+  // gather: thread (slice = tid / 16, col = tid % 16) folds 8 channels of the
+  // chunks slice, slice + 64, ... with 16-byte loads
+  const int col = tid & 15, slice = tid >> 4;
+  const u32x4* p4 = reinterpret_cast<const u32x4*>(ws + hd * chunks * 2 * D) + col;
+  const _Float16 big = (_Float16)65504.0f;
+  h2 mn[4], mx[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) { mn[i] = h2{big, big}; mx[i] = h2{-big, -big}; }
+  for (int k = slice; k < chunks; k += 64) {
+    U4H a, b;
+    a.u = p4[(k * 2) * 16];
+    b.u = p4[(k * 2 + 1) * 16];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      mn[i] = __builtin_elementwise_min(mn[i], a.h[i]);
+      mx[i] = __builtin_elementwise_max(mx[i], b.h[i]);
+    }
   }
-  __shared__ _Float16 slo[8][D], shi[8][D];
+  __shared__ h2 smn[64][16][4];
+  __shared__ h2 smx[64][16][4];
   __shared__ float R[D];
   __shared__ int flag[D];
-  slo[part][c] = lo;
-  shi[part][c] = hi;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) { smn[slice][col][i] = mn[i]; smx[slice][col][i] = mx[i]; }
   __syncthreads();
+  const int c = tid & 127, part = tid >> 7;
   float r = 0.0f;
   if (part == 0) {
-#pragma unroll
-    for (int i = 1; i < 8; ++i) {
-      const _Float16 a = slo[i][c], b = shi[i][c];
+    const int c8 = c >> 3, e = c & 7;
+    _Float16 lo = big, hi = -big;
+    for (int s = 0; s < 64; ++s) {
+      const _Float16 a = smn[s][c8][e >> 1][e & 1];
+      const _Float16 b = smx[s][c8][e >> 1][e & 1];
       lo = a < lo ? a : lo;
       hi = b > hi ? b : hi;
     }

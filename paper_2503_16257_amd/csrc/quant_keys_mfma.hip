@@ -25,6 +25,42 @@ namespace vidkv {
 constexpr int ENC_MAXT = 9;          // channel tiles of 16: at most 1 + 8
 constexpr int ENC_ROW = 272;         // LDS bytes per token row (256 + 16 of padding)
 
+// DFT operand table.  Slot x of tile tt (tt = 0: Re X[0..15]; tt = 1: Re X[16],
+// Im X[1..15]) against token t: 64 * (w/2) * {cos, -sin}(2 pi k t / 32), with
+// w = 1 for the two real-only bins and 2 otherwise, so that the sum of |D| over
+// a channel's slots is 1024 * Mean|.| of Eq. 5; positive row scaling does not
+// change a sign.  Each fp32 entry is split into three fp16 parts that add up to
+// it exactly.  Indexed [tt][part][lane][4 words]: the 8 halves of a lane's
+// MFMA operand (slot x = lane & 15, tokens slot_token(lane >> 4, 0..7)).
+struct DftTab { uint32_t w[2][3][64][4]; };
+
+constexpr uint32_t half_bits(_Float16 h) { return __builtin_bit_cast(uint16_t, h); }
+
+constexpr DftTab make_dft_tab() {
+  DftTab tab{};
+  for (int tt = 0; tt < 2; ++tt)
+    for (int lane = 0; lane < 64; ++lane)
+      for (int i = 0; i < 8; ++i) {
+        const int kb = lane >> 4, k = lane & 15;
+        const int t = (i < 4) ? 4 * kb + i : 16 + 4 * kb + (i - 4);
+        float w = 0.0f;
+        if (tt == 0) w = cos32(k * t) * (k == 0 ? 32.0f : 64.0f);
+        else         w = (k == 0) ? ((t & 1) ? -32.0f : 32.0f) : -cos32(k * t + 24) * 64.0f;
+        if (w == 0.0f) w = 0.0f;                       // no negative zero
+        const _Float16 a = (_Float16)w;
+        const float r1 = w - (float)a;
+        const _Float16 b = (_Float16)r1;
+        const _Float16 c = (_Float16)(r1 - (float)b);
+        const int sh = 16 * (i & 1);
+        tab.w[tt][0][lane][i >> 1] |= half_bits(a) << sh;
+        tab.w[tt][1][lane][i >> 1] |= half_bits(b) << sh;
+        tab.w[tt][2][lane][i >> 1] |= half_bits(c) << sh;
+      }
+  return tab;
+}
+
+static __device__ const DftTab kDftTab = make_dft_tab();
+
 // NA8T >= 0 fixes n_a = 8 * NA8T at compile time (tile loop fully unrolled);
 // NA8T < 0 takes n_a at run time.
 template <int NA8T>
@@ -44,51 +80,8 @@ __global__ __launch_bounds__(256) void k_encode_mfma_kernel(const u32x4* __restr
   __shared__ u32x4 tile4[4][32 * ENC_ROW / 16];   // per wave: the group's tile
   __shared__ u32x4 recbuf[4][1536 / 16];          // per wave: the record being assembled
 
-  // Channel tile j: anomalous tiles first (16 anomalous channels each, in PERM
-  // order), then normal tiles.  My column's channel in every tile, as a byte
-  // offset inside a token row (an absent column reads channel 0 and is ignored).
-  int chofs[ENC_MAXT];
-#pragma unroll
-  for (int j = 0; j < ENC_MAXT; ++j) {
-    const bool an = j < NTa;
-    const int off = an ? 16 * j + x16 : 16 * (j - NTa) + x16;
-    const bool valid = j < NT && (an ? off < n_a : off < n_n);
-    chofs[j] = valid ? 2 * (int)perm_g[hd * D + (an ? off : n_a + off)] : 0;
-  }
-
-  // DFT operand: slot x16 of tile tt (tt = 0: Re X[0..15]; tt = 1: Re X[16], Im X[1..15]),
-  // k-slots = tokens.  Entries are 64 * (w/2) * {cos, -sin}(2 pi k t / 32) with
-  // w = 1 for the two real-only bins and 2 otherwise, so that the sum of |D| over
-  // a channel's slots is 1024 * Mean|.| of Eq. 5; positive row scaling does not
-  // change a sign.  Split into three fp16 parts that add up to the fp32 value.
-  Op F[2][3];
-#pragma unroll
-  for (int tt = 0; tt < 2; ++tt) {
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int t = slot_token(kb, i), k = x16;
-      float w;
-      if (tt == 0) w = kCosT[(k * t) & 31] * (k == 0 ? 32.0f : 64.0f);
-      else         w = (k == 0) ? ((t & 1) ? -32.0f : 32.0f) : -kCosT[(k * t + 24) & 31] * 64.0f;
-      if (w == 0.0f) w = 0.0f;                       // no negative zero
-      const _Float16 a = (_Float16)w;
-      const float r1 = w - (float)a;
-      const _Float16 b = (_Float16)r1;
-      const _Float16 c = (_Float16)(r1 - (float)b);
-      F[tt][0].v[i] = a;
-      F[tt][1].v[i] = b;
-      F[tt][2].v[i] = c;
-    }
-  }
-
-  uint8_t* rec8 = reinterpret_cast<uint8_t*>(&recbuf[wave][0]);
-  uint16_t* rec16 = reinterpret_cast<uint16_t*>(rec8);
-  const int bits_h = 6 * n_a;                        // half-word offsets inside the record
-  const int meta_h = 6 * n_a + 2 * n_n;
-  const int nblk = n_n >> 3;
-  // my 8 token slots start at row 4*kb (slots 0-3) and 16 + 4*kb (slots 4-7)
-  const uint8_t* tcol = reinterpret_cast<const uint8_t*>(&tile4[wave][0]) + 4 * kb * ENC_ROW;
-
+  // the first tile is requested before anything else so that its latency
+  // overlaps the set-up below
   const int g_begin = blockIdx.x * gpb;
   const int g_end = min(ng, g_begin + gpb);
   const u32x4* head = K + hd * (long long)T * 16;
@@ -102,6 +95,34 @@ __global__ __launch_bounds__(256) void k_encode_mfma_kernel(const u32x4* __restr
   };
   int g = g_begin + wave;
   if (g < g_end) prefetch(g);
+
+  // Channel tile j: anomalous tiles first (16 anomalous channels each, in PERM
+  // order), then normal tiles.  My column's channel in every tile, as a byte
+  // offset inside a token row (an absent column reads channel 0 and is ignored).
+  int chofs[ENC_MAXT];
+#pragma unroll
+  for (int j = 0; j < ENC_MAXT; ++j) {
+    const bool an = j < NTa;
+    const int off = an ? 16 * j + x16 : 16 * (j - NTa) + x16;
+    const bool valid = j < NT && (an ? off < n_a : off < n_n);
+    chofs[j] = valid ? 2 * (int)perm_g[hd * D + (an ? off : n_a + off)] : 0;
+  }
+
+  // DFT operand from the precomputed table: slot x16 of tile tt, k-slots = tokens
+  Op F[2][3];
+#pragma unroll
+  for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+    for (int part = 0; part < 3; ++part)
+      F[tt][part].q = *reinterpret_cast<const u32x4*>(&kDftTab.w[tt][part][lane][0]);
+
+  uint8_t* rec8 = reinterpret_cast<uint8_t*>(&recbuf[wave][0]);
+  uint16_t* rec16 = reinterpret_cast<uint16_t*>(rec8);
+  const int bits_h = 6 * n_a;                        // half-word offsets inside the record
+  const int meta_h = 6 * n_a + 2 * n_n;
+  const int nblk = n_n >> 3;
+  // my 8 token slots start at row 4*kb (slots 0-3) and 16 + 4*kb (slots 4-7)
+  const uint8_t* tcol = reinterpret_cast<const uint8_t*>(&tile4[wave][0]) + 4 * kb * ENC_ROW;
 
   for (; g < g_end; g += 4) {
     {
@@ -222,7 +243,9 @@ __global__ __launch_bounds__(256) void k_encode_mfma_kernel(const u32x4* __restr
 }
 
 void launch_k_encode(const Geom& g, const void* K, uint8_t* packed, hipStream_t st) {
-  const int gpb = pick_groups_per_wg(g.ng, g.nheads, 4 * device_cu_count());   // 4 workgroups per CU
+  // two groups per wave: short-lived workgroups keep the memory system evenly loaded,
+  // and the second group's load overlaps the first group's arithmetic
+  const int gpb = 8;
   dim3 grid((g.ng + gpb - 1) / gpb, (unsigned)g.nheads);
   const u32x4* k4 = reinterpret_cast<const u32x4*>(K);
   const uint8_t* perm = packed + g.k_perm;

@@ -40,7 +40,7 @@ __device__ __forceinline__ int block_exscan_256(int v, int* sw, int* total) {
 //
 // From scores: the n_s largest by (score desc, index asc) via a 3-level radix
 // select on the ordered 32-bit keys (11 + 11 + 10 bits).  Each level is one
-// launch: every workgroup histograms its slice of SEL_SLICE tokens in LDS and
+// launch: every workgroup histograms its slice of LV_SLICE tokens in LDS and
 // adds it to a global histogram; the workgroup that finishes last (atomic
 // ticket, nobody waits) scans the histogram from the top and narrows the
 // prefix.  Then a counting launch (selected / tied elements per slice, last
@@ -57,6 +57,7 @@ __device__ __forceinline__ int block_exscan_256(int v, int* sw, int* total) {
 // ---------------------------------------------------------------------------
 constexpr int SEL_SLICE = 8192;                  // tokens per workgroup = 256 groups
 constexpr int SEL_BINS = 2048;
+constexpr int LV_SLICE = 2048;                   // tokens per workgroup of a radix level
 
 struct SelWs {
   int* tick; int* st; int* hist; int* cnt; int* pre;
@@ -110,11 +111,26 @@ __global__ __launch_bounds__(256) void v_sel_level_kernel(const float* __restric
   for (int i = tid; i < NB; i += 256) h[i] = 0;
   const uint32_t prefix = (uint32_t)ld_dev(&w.st[b * 4 + 0]);
   __syncthreads();
-  const float* sc = scores + (size_t)b * T;
-  const int t0 = slice * SEL_SLICE, t1 = min(T, t0 + SEL_SLICE);
-  for (int t = t0 + tid; t < t1; t += 256) {
-    const uint32_t k = fkey(sc[t]);
-    if ((k & PMASK) == prefix) atomicAdd(&h[(k >> SHIFT) & (NB - 1)], 1);
+  // T is a multiple of 32 and the scores are 16-byte aligned: whole float4 pieces,
+  // all requested before the first is used
+  const float4* sc4 = reinterpret_cast<const float4*>(scores + (size_t)b * T);
+  const int p0 = slice * (LV_SLICE / 4), np = T >> 2;
+  float4 v[LV_SLICE / 1024];
+#pragma unroll
+  for (int q = 0; q < LV_SLICE / 1024; ++q) {
+    const int p = p0 + q * 256 + tid;
+    v[q] = p < np ? sc4[p] : float4{0.f, 0.f, 0.f, 0.f};
+  }
+#pragma unroll
+  for (int q = 0; q < LV_SLICE / 1024; ++q) {
+    if (p0 + q * 256 + tid < np) {
+      const float x[4] = {v[q].x, v[q].y, v[q].z, v[q].w};
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const uint32_t k = fkey(x[j]);
+        if ((k & PMASK) == prefix) atomicAdd(&h[(k >> SHIFT) & (NB - 1)], 1);
+      }
+    }
   }
   __syncthreads();
   int* gh = w.hist + ((size_t)b * 3 + LEVEL) * SEL_BINS;
@@ -299,9 +315,10 @@ hipError_t launch_quantize_values(const Geom& g, float gamma, const void* V, con
                        reinterpret_cast<int*>(ws), n_ints, g.B, g.n_s, scores ? nullptr : mask,
                        n_mask);
     if (scores) {
-      hipLaunchKernelGGL(v_sel_level_kernel<0>, gs, dim3(256), 0, st, scores, g.T, w);
-      hipLaunchKernelGGL(v_sel_level_kernel<1>, gs, dim3(256), 0, st, scores, g.T, w);
-      hipLaunchKernelGGL(v_sel_level_kernel<2>, gs, dim3(256), 0, st, scores, g.T, w);
+      dim3 gl((g.T + LV_SLICE - 1) / LV_SLICE, g.B);
+      hipLaunchKernelGGL(v_sel_level_kernel<0>, gl, dim3(256), 0, st, scores, g.T, w);
+      hipLaunchKernelGGL(v_sel_level_kernel<1>, gl, dim3(256), 0, st, scores, g.T, w);
+      hipLaunchKernelGGL(v_sel_level_kernel<2>, gl, dim3(256), 0, st, scores, g.T, w);
       hipLaunchKernelGGL(v_sel_count_kernel<false>, gs, dim3(256), 0, st, scores, mask, g.T, g.ng, w);
       hipLaunchKernelGGL(v_sel_mark_kernel<false>, gs, dim3(256), 0, st, scores, g.T, g.ng, g.n_s,
                          w, idx_out, mask, rank);

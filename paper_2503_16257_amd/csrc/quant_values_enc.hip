@@ -157,7 +157,8 @@ __global__ __launch_bounds__(256) void v_encode_wave_kernel(const u32x4* __restr
 }
 
 void launch_v_encode(const Geom& g, float gamma, const void* V, uint8_t* packed, hipStream_t st) {
-  const int gpb = pick_groups_per_wg(g.ng, g.nheads, 4 * device_cu_count());   // 4 workgroups per CU
+  // one group per wave: many short-lived workgroups balance the memory system best here
+  const int gpb = 4;
   dim3 grid((g.ng + gpb - 1) / gpb, (unsigned)g.nheads);
   hipLaunchKernelGGL(v_encode_wave_kernel, grid, dim3(256), 0, st, reinterpret_cast<const u32x4*>(V),
                      g.T, g.ng, g.B, g.H, g.n_s, gamma, gpb,

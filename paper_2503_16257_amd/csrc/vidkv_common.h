@@ -88,33 +88,6 @@ inline bool make_geom(const vidkv_params* p, Geom* g) {
   return true;
 }
 
-// Groups per workgroup for the wave-per-group coding kernels (4 waves each):
-// the smallest number of rounds over `slots` concurrently resident workgroups,
-// and among equal costs the largest workgroup (fewer prologues).
-inline int pick_groups_per_wg(int ng, long long nheads, int slots) {
-  int best = 4;
-  long long best_cost = -1;
-  for (int gpb = 4; gpb <= 32; gpb += 4) {
-    const long long nwg = (long long)((ng + gpb - 1) / gpb) * nheads;
-    const long long cost = ((nwg + slots - 1) / slots) * gpb;
-    if (best_cost < 0 || cost <= best_cost) { best_cost = cost; best = gpb; }
-  }
-  return best;
-}
-
-inline int device_cu_count() {
-  static int cus = 0;
-  if (cus == 0) {
-    int dev = 0, n = 0;
-    if (hipGetDevice(&dev) == hipSuccess &&
-        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
-      cus = n;
-    else
-      cus = 256;
-  }
-  return cus;
-}
-
 // cos / sin of 2 pi j / 32 from one first-octant table (values rounded to
 // fp32), with the symmetries applied exactly so that quarter-turn values are
 // exactly 0 and +-1.  All uses pass compile-time j.

@@ -26,7 +26,11 @@
  *    (Hq % Hkv == 0, Hq / Hkv <= 8; query head h reads KV head h / (Hq/Hkv)),
  *    D = head_dim = 128, G = group = 32, Tq = t_quant (multiple of 32).
  *  - The packed buffers are opaque to the caller; their byte sizes come from
- *    the vidkv_packed_*_bytes functions.  Buffers must be 256-byte aligned.
+ *    the vidkv_packed_*_bytes functions.  Packed buffers and workspaces must
+ *    be 256-byte aligned; fp16 tensors and the saliency scores 16-byte
+ *    aligned; int32 arrays 4-byte aligned (else VIDKV_EINVAL).
+ *  - A workspace is scratch: undefined contents on entry and exit, not to be
+ *    shared by calls that may run at the same time.
  */
 #ifndef VIDKV_H
 #define VIDKV_H

@@ -85,38 +85,60 @@ __global__ __launch_bounds__(1024) void k_select_kernel(const _Float16* __restri
                                                         int chunks, int n_a,
                                                         uint8_t* __restrict__ perm) {
   const long long hd = blockIdx.x;
-  const int tid = threadIdx.x;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   // gather: thread (slice = tid / 16, col = tid % 16) folds 8 channels of the
-  // chunks slice, slice + 64, ... with 16-byte loads
+  // chunks slice, slice + 64, ... with 16-byte loads, 4 chunks in flight
   const int col = tid & 15, slice = tid >> 4;
   const u32x4* p4 = reinterpret_cast<const u32x4*>(ws + hd * chunks * 2 * D) + col;
   const _Float16 big = (_Float16)65504.0f;
   h2 mn[4], mx[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) { mn[i] = h2{big, big}; mx[i] = h2{-big, -big}; }
-  for (int k = slice; k < chunks; k += 64) {
-    U4H a, b;
-    a.u = p4[(k * 2) * 16];
-    b.u = p4[(k * 2 + 1) * 16];
+  for (int k0 = slice; k0 < chunks; k0 += 256) {
+    U4H a[4], b[4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      mn[i] = __builtin_elementwise_min(mn[i], a.h[i]);
-      mx[i] = __builtin_elementwise_max(mx[i], b.h[i]);
+    for (int u = 0; u < 4; ++u) {
+      const int k = k0 + 64 * u;
+      const int kk = k < chunks ? k : k0;             // a repeated chunk changes nothing
+      a[u].u = p4[(kk * 2) * 16];
+      b[u].u = p4[(kk * 2 + 1) * 16];
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        mn[i] = __builtin_elementwise_min(mn[i], a[u].h[i]);
+        mx[i] = __builtin_elementwise_max(mx[i], b[u].h[i]);
+      }
+  }
+  // the 4 slices of a wave (lanes 16 apart), then the 16 waves through LDS
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+#pragma unroll
+    for (int d = 16; d <= 32; d <<= 1) {
+      mn[i] = __builtin_elementwise_min(mn[i], __builtin_bit_cast(h2, __shfl_xor(__builtin_bit_cast(int, mn[i]), d, 64)));
+      mx[i] = __builtin_elementwise_max(mx[i], __builtin_bit_cast(h2, __shfl_xor(__builtin_bit_cast(int, mx[i]), d, 64)));
     }
   }
-  __shared__ h2 smn[64][16][4];
-  __shared__ h2 smx[64][16][4];
+  __shared__ h2 smn[16][16][4];
+  __shared__ h2 smx[16][16][4];
   __shared__ float R[D];
-  __shared__ int flag[D];
+  __shared__ int cnt0;
+  if (lane < 16) {
 #pragma unroll
-  for (int i = 0; i < 4; ++i) { smn[slice][col][i] = mn[i]; smx[slice][col][i] = mx[i]; }
+    for (int i = 0; i < 4; ++i) { smn[wave][col][i] = mn[i]; smx[wave][col][i] = mx[i]; }
+  }
   __syncthreads();
-  const int c = tid & 127, part = tid >> 7;
+  // from here on threads 0..127 (waves 0 and 1) own one channel each; the other
+  // waves only keep the barriers company
+  const int c = tid & (D - 1);
+  const bool own = tid < D;
   float r = 0.0f;
-  if (part == 0) {
+  if (own) {
     const int c8 = c >> 3, e = c & 7;
     _Float16 lo = big, hi = -big;
-    for (int s = 0; s < 64; ++s) {
+#pragma unroll
+    for (int s = 0; s < 16; ++s) {
       const _Float16 a = smn[s][c8][e >> 1][e & 1];
       const _Float16 b = smx[s][c8][e >> 1][e & 1];
       lo = a < lo ? a : lo;
@@ -126,20 +148,23 @@ __global__ __launch_bounds__(1024) void k_select_kernel(const _Float16* __restri
     R[c] = r;
   }
   __syncthreads();
-  int an = 0;
-  if (part == 0) {
+  int an = 0, below = 0;
+  if (own) {
     int rank = 0;
+#pragma unroll 16
     for (int j = 0; j < D; ++j) {
       const float rj = R[j];
       rank += (rj > r || (rj == r && j < c)) ? 1 : 0;
     }
     an = rank < n_a ? 1 : 0;
-    flag[c] = an;
   }
+  // anomalous channels below mine: inside my wave by ballot, wave 0's total through LDS
+  const unsigned long long bal = __ballot(an);
+  below = __popcll(bal & ((1ull << lane) - 1ull));
+  if (tid == 0) cnt0 = __popcll(bal);
   __syncthreads();
-  if (part == 0) {
-    int below = 0;
-    for (int j = 0; j < c; ++j) below += flag[j];
+  if (own) {
+    if (wave == 1) below += cnt0;
     const int pos = an ? below : n_a + (c - below);
     perm[hd * D + pos] = (uint8_t)c;
   }

@@ -41,78 +41,90 @@ __device__ __forceinline__ int block_exscan_256(int v, int* sw, int* total) {
 // From scores: the n_s largest by (score desc, index asc) via a 3-level radix
 // select on the ordered 32-bit keys (11 + 11 + 10 bits).  Each level is one
 // launch: every workgroup histograms its slice of LV_SLICE tokens in LDS and
-// adds it to a global histogram; the workgroup that finishes last (atomic
-// ticket, nobody waits) scans the histogram from the top and narrows the
-// prefix.  Then a counting launch (selected / tied elements per slice, last
-// workgroup turns them into exclusive prefixes) and a marking launch that
-// writes MASK, RANK and IDX.  From an index list: MASK is zeroed and set by
-// atomics, then the same counting and marking launches run on the mask.
+// adds it to that level's global histogram.  Nobody waits inside a launch: the
+// scan of a level's histogram (which bin holds the remaining-th largest key) is
+// done by every workgroup of the NEXT launch at its start, redundantly, while
+// its score loads are in flight; the first workgroup also records the narrowed
+// (prefix, remaining) pair for the launch after.  Then a counting launch
+// (selected / tied elements per slice of SEL_SLICE tokens) and a marking launch
+// that sums the counts of the slices before its own and writes MASK, RANK and
+// IDX.  From an index list: MASK is zeroed and set by atomics, then the same
+// counting and marking launches run on the mask.
 //
 // Workspace (ints): per sequence b
-//   tick[b][4]                 completion tickets of the 3 levels + counting
-//   st[b][4]                   prefix, remaining, (unused)
+//   st[b][3][2]                (prefix, remaining) after the scan of level 0, 1, 2
 //   hist[b][3][2048]
 //   cnt[b][nslice][2]          selected, tied          (per slice)
-//   pre[b][nslice][2]          exclusive prefixes of the above
 // ---------------------------------------------------------------------------
 constexpr int SEL_SLICE = 8192;                  // tokens per workgroup = 256 groups
 constexpr int SEL_BINS = 2048;
 constexpr int LV_SLICE = 2048;                   // tokens per workgroup of a radix level
 
 struct SelWs {
-  int* tick; int* st; int* hist; int* cnt; int* pre;
+  int* st; int* hist; int* cnt;
   int nslice;
 };
 
 __host__ __device__ inline size_t sel_ws_ints(int B, int nslice) {
-  return (size_t)B * (4 + 4 + 3 * SEL_BINS + 4 * (size_t)nslice);
+  return (size_t)B * (8 + 3 * SEL_BINS + 2 * (size_t)nslice);
 }
 
 __device__ __host__ inline SelWs sel_ws(void* ws, int B, int nslice) {
   SelWs w;
   int* p = reinterpret_cast<int*>(ws);
-  w.tick = p;  p += (size_t)B * 4;
-  w.st = p;    p += (size_t)B * 4;
-  w.hist = p;  p += (size_t)B * 3 * SEL_BINS;
-  w.cnt = p;   p += (size_t)B * nslice * 2;
-  w.pre = p;
+  w.hist = p;  p += (size_t)B * 3 * SEL_BINS;       // zeroed by the init launch
+  w.st = p;    p += (size_t)B * 8;
+  w.cnt = p;
   w.nslice = nslice;
   return w;
 }
 
-__global__ __launch_bounds__(256) void v_sel_init_kernel(int* __restrict__ ws, size_t n_ints,
-                                                         int B, int n_s,
+// zeroes the histograms (and, for the index-list path, MASK)
+__global__ __launch_bounds__(256) void v_sel_init_kernel(int* __restrict__ hist, size_t n_ints,
                                                          uint32_t* __restrict__ mask, size_t n_mask) {
   const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-  if (i < n_ints) {
-    // st[b][1] starts as "remaining = n_s"; everything else is 0
-    const size_t st0 = (size_t)B * 4;
-    int v = 0;
-    if (i >= st0 && i < st0 + (size_t)B * 4 && ((i - st0) & 3) == 1) v = n_s;
-    ws[i] = v;
-  }
+  if (i < n_ints) hist[i] = 0;
   if (mask && i < n_mask) mask[i] = 0;
 }
 
-__device__ __forceinline__ int ld_dev(const int* p) {
-  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+// Which bin of a finished histogram holds the rem-th largest key, and which
+// rank it has inside that bin.  All 256 threads of the block call this; thread
+// t owns the PER bins of group 255 - t, so an exclusive scan over threads gives
+// the count of keys in all higher bins.  sres[0] = bin, sres[1] = new remaining.
+template <int NB>
+__device__ __forceinline__ void find_bin(const int* __restrict__ gh, int rem, int* sw, int* sres) {
+  constexpr int PER = NB / 256;
+  const int grp = 255 - (int)threadIdx.x;
+  int c[PER];
+  int mine = 0;
+#pragma unroll
+  for (int i = 0; i < PER; ++i) { c[i] = gh[grp * PER + i]; mine += c[i]; }
+  int tot;
+  const int above = block_exscan_256(mine, sw, &tot);
+  if (above < rem && rem <= above + mine) {          // exactly one thread
+    int r = rem - above, i = PER - 1;
+#pragma unroll
+    for (int k = PER - 1; k > 0; --k)
+      if (i == k && c[k] < r) { r -= c[k]; i = k - 1; }
+    sres[0] = grp * PER + i;
+    sres[1] = r;
+  }
+  __syncthreads();
 }
 
 template <int LEVEL>
 __global__ __launch_bounds__(256) void v_sel_level_kernel(const float* __restrict__ scores, int T,
-                                                          SelWs w) {
+                                                          int n_s, SelWs w) {
   constexpr int SHIFT = LEVEL == 0 ? 21 : (LEVEL == 1 ? 10 : 0);
   constexpr int NB = LEVEL == 2 ? 1024 : 2048;
   constexpr uint32_t PMASK = LEVEL == 0 ? 0u : (LEVEL == 1 ? 0xFFE00000u : 0xFFFFFC00u);
   const int b = blockIdx.y, slice = blockIdx.x, tid = threadIdx.x;
   __shared__ int h[SEL_BINS];
-  __shared__ int cum[256];
-  __shared__ int s_last;
+  __shared__ int sw[4];
+  __shared__ int sres[2];
   for (int i = tid; i < NB; i += 256) h[i] = 0;
-  const uint32_t prefix = (uint32_t)ld_dev(&w.st[b * 4 + 0]);
-  __syncthreads();
   // T is a multiple of 32 and the scores are 16-byte aligned: whole float4 pieces,
-  // all requested before the first is used
+  // all requested before anything else
   const float4* sc4 = reinterpret_cast<const float4*>(scores + (size_t)b * T);
   const int p0 = slice * (LV_SLICE / 4), np = T >> 2;
   float4 v[LV_SLICE / 1024];
@@ -120,6 +132,20 @@ __global__ __launch_bounds__(256) void v_sel_level_kernel(const float* __restric
   for (int q = 0; q < LV_SLICE / 1024; ++q) {
     const int p = p0 + q * 256 + tid;
     v[q] = p < np ? sc4[p] : float4{0.f, 0.f, 0.f, 0.f};
+  }
+  // the previous level's result: scan its histogram (every workgroup, redundantly)
+  uint32_t prefix = 0;
+  if (LEVEL == 1) {
+    find_bin<2048>(w.hist + ((size_t)b * 3 + 0) * SEL_BINS, n_s, sw, sres);
+    prefix = (uint32_t)sres[0] << 21;
+    if (slice == 0 && tid == 0) { w.st[b * 8 + 0] = (int)prefix; w.st[b * 8 + 1] = sres[1]; }
+  } else if (LEVEL == 2) {
+    const uint32_t p1 = (uint32_t)w.st[b * 8 + 0];
+    find_bin<2048>(w.hist + ((size_t)b * 3 + 1) * SEL_BINS, w.st[b * 8 + 1], sw, sres);
+    prefix = p1 | ((uint32_t)sres[0] << 10);
+    if (slice == 0 && tid == 0) { w.st[b * 8 + 2] = (int)prefix; w.st[b * 8 + 3] = sres[1]; }
+  } else {
+    __syncthreads();
   }
 #pragma unroll
   for (int q = 0; q < LV_SLICE / 1024; ++q) {
@@ -136,32 +162,6 @@ __global__ __launch_bounds__(256) void v_sel_level_kernel(const float* __restric
   int* gh = w.hist + ((size_t)b * 3 + LEVEL) * SEL_BINS;
   for (int i = tid; i < NB; i += 256)
     if (h[i]) atomicAdd(&gh[i], h[i]);
-  __threadfence();
-  __syncthreads();
-  if (tid == 0) s_last = (atomicAdd(&w.tick[b * 4 + LEVEL], 1) == (int)gridDim.x - 1) ? 1 : 0;
-  __syncthreads();
-  if (!s_last) return;
-  __threadfence();
-  // last workgroup of this sequence: find the bin that holds the remaining-th
-  // largest key.  Thread t owns the PER bins of group 255 - t, so an exclusive
-  // scan over threads gives the count of keys in all higher bins.
-  constexpr int PER = NB / 256;
-  const int grp = 255 - tid;
-  int c[PER];
-  int mine = 0;
-#pragma unroll
-  for (int i = 0; i < PER; ++i) { c[i] = ld_dev(&gh[grp * PER + i]); mine += c[i]; }
-  const int rem = ld_dev(&w.st[b * 4 + 1]);
-  int tot;
-  const int above = block_exscan_256(mine, cum, &tot);
-  if (above < rem && rem <= above + mine) {          // exactly one thread
-    int r = rem - above, i = PER - 1;
-#pragma unroll
-    for (int k = PER - 1; k > 0; --k)
-      if (i == k && c[k] < r) { r -= c[k]; i = k - 1; }
-    w.st[b * 4 + 0] = (int)(prefix | ((uint32_t)(grp * PER + i) << SHIFT));
-    w.st[b * 4 + 1] = r;
-  }
 }
 
 // Flags of one 32-token group: bit j set = token selected-or-tied information.
@@ -170,7 +170,7 @@ template <bool FROM_MASK>
 __device__ __forceinline__ void group_flags(const float* sc, const uint32_t* mk, int g,
                                             uint32_t kth, uint32_t* sel, uint32_t* tie) {
   if (FROM_MASK) {
-    *sel = __hip_atomic_load(&mk[g], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    *sel = mk[g];
     *tie = 0;
   } else {
     uint32_t s = 0, e = 0;
@@ -197,10 +197,17 @@ __global__ __launch_bounds__(256) void v_sel_count_kernel(const float* __restric
                                                           int ng, SelWs w) {
   const int b = blockIdx.y, slice = blockIdx.x, tid = threadIdx.x;
   __shared__ int sw[4];
-  __shared__ int s_last;
+  __shared__ int sres[2];
+  uint32_t kth = 0;
+  if (!FROM_MASK) {
+    // the last radix level's result: the n_s-th largest key and how many of its ties to take
+    const uint32_t p2 = (uint32_t)w.st[b * 8 + 2];
+    find_bin<1024>(w.hist + ((size_t)b * 3 + 2) * SEL_BINS, w.st[b * 8 + 3], sw, sres);
+    kth = p2 | (uint32_t)sres[0];
+    if (slice == 0 && tid == 0) { w.st[b * 8 + 4] = (int)kth; w.st[b * 8 + 5] = sres[1]; }
+  }
   const int g = slice * (SEL_SLICE / G) + tid;
   uint32_t sel = 0, tie = 0;
-  const uint32_t kth = (uint32_t)ld_dev(&w.st[b * 4 + 0]);
   if (g < ng) group_flags<FROM_MASK>(scores + (size_t)b * T, mask + (size_t)b * ng, g, kth, &sel, &tie);
   int tot_s, tot_e;
   block_exscan_256(__popc(sel), sw, &tot_s);
@@ -208,27 +215,6 @@ __global__ __launch_bounds__(256) void v_sel_count_kernel(const float* __restric
   if (tid == 0) {
     w.cnt[((size_t)b * w.nslice + slice) * 2 + 0] = tot_s;
     w.cnt[((size_t)b * w.nslice + slice) * 2 + 1] = tot_e;
-    __threadfence();
-    s_last = (atomicAdd(&w.tick[b * 4 + 3], 1) == (int)gridDim.x - 1) ? 1 : 0;
-  }
-  __syncthreads();
-  if (!s_last) return;
-  __threadfence();
-  // exclusive prefixes over the slices, 256 slices at a time
-  int carry_s = 0, carry_e = 0;
-  for (int i0 = 0; i0 < w.nslice; i0 += 256) {
-    const int i = i0 + tid;
-    const int cs = i < w.nslice ? ld_dev(&w.cnt[((size_t)b * w.nslice + i) * 2 + 0]) : 0;
-    const int ce = i < w.nslice ? ld_dev(&w.cnt[((size_t)b * w.nslice + i) * 2 + 1]) : 0;
-    int ts, te;
-    const int ps = block_exscan_256(cs, sw, &ts);
-    const int pe = block_exscan_256(ce, sw, &te);
-    if (i < w.nslice) {
-      w.pre[((size_t)b * w.nslice + i) * 2 + 0] = carry_s + ps;
-      w.pre[((size_t)b * w.nslice + i) * 2 + 1] = carry_e + pe;
-    }
-    carry_s += ts;
-    carry_e += te;
   }
 }
 
@@ -242,14 +228,25 @@ __global__ __launch_bounds__(256) void v_sel_mark_kernel(const float* __restrict
   __shared__ int sw[4];
   const int g = slice * (SEL_SLICE / G) + tid;
   uint32_t sel = 0, tie = 0;
-  const uint32_t kth = (uint32_t)w.st[b * 4 + 0];
-  const int take_eq = w.st[b * 4 + 1];            // tied elements to take, lowest index first
+  const uint32_t kth = FROM_MASK ? 0u : (uint32_t)w.st[b * 8 + 4];
+  const int take_eq = FROM_MASK ? 0 : w.st[b * 8 + 5];   // tied elements to take, lowest index first
+  // selected / tied elements in the slices before mine
+  int pre_s = 0, pre_e = 0;
+  for (int i0 = 0; i0 < slice; i0 += 256) {
+    const int i = i0 + tid;
+    const int cs = i < slice ? w.cnt[((size_t)b * w.nslice + i) * 2 + 0] : 0;
+    const int ce = i < slice ? w.cnt[((size_t)b * w.nslice + i) * 2 + 1] : 0;
+    int ts, te;
+    block_exscan_256(cs, sw, &ts);
+    block_exscan_256(ce, sw, &te);
+    pre_s += ts;
+    pre_e += te;
+  }
   uint32_t* mk = mask + (size_t)b * ng;
   if (g < ng) group_flags<FROM_MASK>(scores + (size_t)b * T, mk, g, kth, &sel, &tie);
   int tot;
   // ties: take those whose (global, index-ordered) tie number is below take_eq
-  int tie_before = w.pre[((size_t)b * w.nslice + slice) * 2 + 1] +
-                   block_exscan_256(__popc(tie), sw, &tot);
+  int tie_before = pre_e + block_exscan_256(__popc(tie), sw, &tot);
   uint32_t e = tie;
   while (e) {
     const int j = __ffs(e) - 1;
@@ -259,8 +256,8 @@ __global__ __launch_bounds__(256) void v_sel_mark_kernel(const float* __restrict
   }
   // number of protected tokens before this group: selected-above-kth before
   // the slice + ties taken before the slice + the same inside the slice
-  const int ties_before_slice = min(w.pre[((size_t)b * w.nslice + slice) * 2 + 1], take_eq);
-  int before = w.pre[((size_t)b * w.nslice + slice) * 2 + 0] + (FROM_MASK ? 0 : ties_before_slice) +
+  const int ties_before_slice = min(pre_e, take_eq);
+  int before = pre_s + (FROM_MASK ? 0 : ties_before_slice) +
                block_exscan_256(__popc(sel), sw, &tot);
   if (g < ng) {
     if (!FROM_MASK) mk[g] = sel;
@@ -306,19 +303,18 @@ hipError_t launch_quantize_values(const Geom& g, float gamma, const void* V, con
   if (g.n_s > 0 && (stages & 1u)) {
     const int nslice = (g.T + SEL_SLICE - 1) / SEL_SLICE;
     SelWs w = sel_ws(ws, g.B, nslice);
-    const size_t n_ints = sel_ws_ints(g.B, nslice);
+    const size_t n_hist = (size_t)g.B * 3 * SEL_BINS;
     const size_t n_mask = (size_t)g.B * g.ng;
-    const size_t n_init = scores ? n_ints : (n_ints > n_mask ? n_ints : n_mask);
+    const size_t n_init = scores ? n_hist : n_mask;
     int32_t* idx_out = reinterpret_cast<int32_t*>(packed + g.v_idx);
     dim3 gs(nslice, g.B);
     hipLaunchKernelGGL(v_sel_init_kernel, dim3((unsigned)((n_init + 255) / 256)), dim3(256), 0, st,
-                       reinterpret_cast<int*>(ws), n_ints, g.B, g.n_s, scores ? nullptr : mask,
-                       n_mask);
+                       w.hist, scores ? n_hist : 0, scores ? nullptr : mask, n_mask);
     if (scores) {
       dim3 gl((g.T + LV_SLICE - 1) / LV_SLICE, g.B);
-      hipLaunchKernelGGL(v_sel_level_kernel<0>, gl, dim3(256), 0, st, scores, g.T, w);
-      hipLaunchKernelGGL(v_sel_level_kernel<1>, gl, dim3(256), 0, st, scores, g.T, w);
-      hipLaunchKernelGGL(v_sel_level_kernel<2>, gl, dim3(256), 0, st, scores, g.T, w);
+      hipLaunchKernelGGL(v_sel_level_kernel<0>, gl, dim3(256), 0, st, scores, g.T, g.n_s, w);
+      hipLaunchKernelGGL(v_sel_level_kernel<1>, gl, dim3(256), 0, st, scores, g.T, g.n_s, w);
+      hipLaunchKernelGGL(v_sel_level_kernel<2>, gl, dim3(256), 0, st, scores, g.T, g.n_s, w);
       hipLaunchKernelGGL(v_sel_count_kernel<false>, gs, dim3(256), 0, st, scores, mask, g.T, g.ng, w);
       hipLaunchKernelGGL(v_sel_mark_kernel<false>, gs, dim3(256), 0, st, scores, g.T, g.ng, g.n_s,
                          w, idx_out, mask, rank);

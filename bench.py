@@ -24,6 +24,17 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 BYTES_V_PER_ELEM = 0.2625      # 1.6-bit trits + one fp16 scale per 32 elements
 
+# HBM bytes per launch (read + written) from hardware counters: rocprofv3 --pmc
+# FETCH_SIZE and WRITE_SIZE, one counter per run, each kernel alone, scaled by
+# what the same counters read for the library's copy kernel of known size
+# (FETCH_SIZE x 2.000, WRITE_SIZE x 1.000).  The runs and their commands are
+# summarized in profiles/c4_long_hbm_traffic.md; a workload that was not
+# counted reports null.
+MEASURED_TRAFFIC_BYTES = {
+    "c4_long": {"k_range": 200.75e6 + 0.78e6, "k_encode": 200.87e6 + 26.66e6,
+                "v_encode": 201.59e6 + 41.40e6, "attn_partial": 68.49e6 + 1.86e6},
+}
+
 
 def algorithmic_bytes(w):
     """Bytes the method itself must move, per kernel, for workload w."""
@@ -209,8 +220,11 @@ def main():
 
     def roof(name, per_launch_div=1.0):
         a = ab[name] / per_launch_div / kt[name] / 1e9
+        tr = MEASURED_TRAFFIC_BYTES.get(w.name, {}).get(name)
         return {"kernel": name, "bound": "hbm", "achieved": round(a, 1), "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": round(a / HBM_PEAK_GBS, 4), "traffic": None,
+                "unit": "GB/s", "frac": round(a / HBM_PEAK_GBS, 4),
+                "traffic": None if tr is None else round(tr),
+                "algorithmic_bytes": round(ab[name] / per_launch_div),
                 "us": round(kt[name] * 1e6, 2)}
 
     roofs = [roof("k_range"), roof("k_encode"), roof("v_encode"), roof("attn_partial", w.L)]

@@ -42,7 +42,7 @@
 extern "C" {
 #endif
 
-#define VIDKV_ABI_VERSION 1
+#define VIDKV_ABI_VERSION 2
 
 typedef enum {
   VIDKV_OK = 0,
@@ -69,6 +69,11 @@ typedef struct vidkv_params {
                             (n = p * l_v of Sec. 3.3 (2))                       */
   float gamma;           /* ternary threshold factor of Eq. 6 (paper: 0.7)      */
   float softmax_scale;   /* multiplies q.k before the softmax (1/sqrt(128))     */
+  int32_t t_capacity;    /* 0: same as t_quant.  Otherwise >= t_quant, multiple
+                            of 32: the packed buffers are laid out (and sized)
+                            for this many tokens so that vidkv_flush_residual
+                            can append blocks in place; every call on the same
+                            buffers must pass the same t_capacity              */
 } vidkv_params;
 
 /* Size queries: pure host functions, usable without a GPU.  Return 0 when
@@ -137,6 +142,31 @@ vidkv_status vidkv_decode_attention(const vidkv_params *params, int32_t layer,
                                     const int32_t *tail_len_dev, void *out_dev,
                                     void *workspace_dev, size_t workspace_bytes,
                                     void *hip_stream);
+
+/* Alg. 1, Decoding, the step taken when the residual buffers are full (R
+ * tokens): the first n_flush residual tokens of every sequence of one layer
+ * are coded and appended to the packed buffers as tokens t_quant ..
+ * t_quant + n_flush - 1.  Values: Alg. 2's 1.58Quant without protected tokens
+ * (Eq. 6).  Keys: the group coding of Alg. 3 (Eq. 4 / Eq. 5) with the channel
+ * split chosen when the cache was first quantized - the ranking by range is
+ * not repeated, and the groups already packed are not touched (re-coding their
+ * dequantized values with the same split would reproduce them).
+ *   params          : t_quant = tokens packed so far (> 0), t_capacity >=
+ *                     t_quant + n_flush
+ *   layer           : 0..L-1
+ *   K_tail_dev, V_tail_dev in : [B, Hkv, tail_capacity, 128] fp16 of this layer;
+ *                     rows 0..n_flush-1 of every head must be valid tokens
+ *   n_flush         : multiple of 32, 0 < n_flush <= tail_capacity
+ *   packed_K_dev, packed_V_dev in/out : as written by the quantize calls with
+ *                     the same t_capacity
+ * Afterwards the caller raises t_quant by n_flush - once every layer has been
+ * flushed - and moves any remaining residual rows to the front.  No workspace. */
+vidkv_status vidkv_flush_residual(const vidkv_params *params, int32_t layer,
+                                  const void *K_tail_dev, const void *V_tail_dev,
+                                  int32_t tail_capacity, int32_t n_flush,
+                                  void *packed_K_dev, size_t packed_K_bytes,
+                                  void *packed_V_dev, size_t packed_V_bytes,
+                                  void *hip_stream);
 
 /* Measurement aids, not part of the method.  Each takes the arguments of the
  * entry point it is named after, checks them the same way, and launches only

@@ -186,17 +186,32 @@ def fft1bit_dequant(bits: np.ndarray, sre16: np.ndarray, sim16: np.ndarray) -> n
 # --------------------------------------------------------------------------
 # Keys: MixQuant (Alg. 3) = selection + 2-bit anomalous + FFT 1-bit normal
 # --------------------------------------------------------------------------
+def quantize_keys_block(K16: np.ndarray, anom: np.ndarray, norm: np.ndarray) -> dict:
+    """The group coding of Alg. 3 for [T, D] tokens with a GIVEN channel split:
+    Eq. 4 at 2 bits on the anomalous channels, Eq. 5 on the others.
+
+    This is also the residual flush of Alg. 1 (Decoding, the branch taken when
+    the residual buffer holds R tokens) under this build's reading: the block
+    of new tokens is coded with the split chosen at prefill and appended; both
+    codes are local to a 32-token group, so earlier groups are not affected.
+    """
+    a = gquant(K16[:, anom], bits=2)
+    n = fft1bit_quant(K16[:, norm])
+    return {
+        "anom": anom, "norm": norm, "perm": np.concatenate([anom, norm]).astype(np.int64),
+        "a_codes": a["codes"], "a_s16": a["s16"], "a_z16": a["z16"], "a_near": a["near"],
+        "n_bits": n["bits"], "n_sre16": n["sre16"], "n_sim16": n["sim16"], "n_near": n["near"],
+    }
+
+
 def quantize_keys_head(K16: np.ndarray, n_a: int):
     """Alg. 3 for one [T, D] head.  Returns the logical (unpacked) cache record."""
     R = key_channel_range(K16)
     anom, norm, perm = select_anomalous_channels(R, n_a)
-    a = gquant(K16[:, anom], bits=2)
-    n = fft1bit_quant(K16[:, norm])
-    return {
-        "range": R, "anom": anom, "norm": norm, "perm": perm,
-        "a_codes": a["codes"], "a_s16": a["s16"], "a_z16": a["z16"], "a_near": a["near"],
-        "n_bits": n["bits"], "n_sre16": n["sre16"], "n_sim16": n["sim16"], "n_near": n["near"],
-    }
+    rec = quantize_keys_block(K16, anom, norm)
+    rec["range"] = R
+    rec["perm"] = perm
+    return rec
 
 
 def dequantize_keys_head(rec: dict) -> np.ndarray:

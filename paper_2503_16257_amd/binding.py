@@ -23,6 +23,7 @@ class VidkvParams(C.Structure):
         ("n_q_heads", C.c_int32), ("head_dim", C.c_int32), ("group", C.c_int32),
         ("t_quant", C.c_int32), ("n_anom", C.c_int32), ("use_fft", C.c_int32),
         ("n_salient", C.c_int32), ("gamma", C.c_float), ("softmax_scale", C.c_float),
+        ("t_capacity", C.c_int32),
     ]
 
 
@@ -55,6 +56,8 @@ def lib() -> C.CDLL:
         L.vidkv_quantize_keys.restype = C.c_int
         L.vidkv_quantize_values.argtypes = [PP, vp, vp, vp, vp, sz, vp, sz, vp]
         L.vidkv_quantize_values.restype = C.c_int
+        L.vidkv_flush_residual.argtypes = [PP, i32, vp, vp, i32, i32, vp, sz, vp, sz, vp]
+        L.vidkv_flush_residual.restype = C.c_int
         L.vidkv_decode_attention.argtypes = [PP, i32, vp, vp, vp, vp, vp, i32, vp, vp, vp, sz, vp]
         L.vidkv_decode_attention.restype = C.c_int
         u32 = C.c_uint32
@@ -76,11 +79,12 @@ def lib() -> C.CDLL:
 
 
 def make_params(n_layers, batch, n_kv_heads, n_q_heads, t_quant, n_anom, n_salient,
-                gamma=0.7, softmax_scale=None, head_dim=128, group=32, use_fft=1) -> VidkvParams:
+                gamma=0.7, softmax_scale=None, head_dim=128, group=32, use_fft=1,
+                t_capacity=0) -> VidkvParams:
     if softmax_scale is None:
         softmax_scale = 1.0 / math.sqrt(head_dim)
     return VidkvParams(n_layers, batch, n_kv_heads, n_q_heads, head_dim, group, t_quant, n_anom,
-                       use_fft, n_salient, gamma, softmax_scale)
+                       use_fft, n_salient, gamma, softmax_scale, t_capacity)
 
 
 def status_string(status: int) -> str:
@@ -174,6 +178,17 @@ def decode_attention(p: VidkvParams, layer: int, q, packed_K, packed_V, out, wor
     else:
         _check(lib().vidkv_decode_attention_stages(*a, stages, _stream(stream)),
                "vidkv_decode_attention_stages")
+
+
+def flush_residual(p: VidkvParams, layer: int, K_tail, V_tail, tail_capacity: int, n_flush: int,
+                   packed_K, packed_V, stream=None) -> None:
+    """vidkv_flush_residual: code the first n_flush residual tokens of one layer and append them."""
+    import torch
+    _check(lib().vidkv_flush_residual(
+        C.byref(p), layer, _ptr(K_tail, torch.float16, "K_tail"), _ptr(V_tail, torch.float16, "V_tail"),
+        tail_capacity, n_flush, _ptr(packed_K, torch.uint8, "packed_K"), _nbytes(packed_K),
+        _ptr(packed_V, torch.uint8, "packed_V"), _nbytes(packed_V), _stream(stream)),
+        "vidkv_flush_residual")
 
 
 def calib_copy(dst, src, stream=None) -> None:

@@ -9,14 +9,15 @@ struct AttnArgs {
   const uint8_t* kperm;      // key PERM section (whole buffer)
   const uint8_t* krec;       // key REC section (whole buffer)
   const uint8_t* vrec;       // value REC section (whole buffer)
-  const uint32_t* vmask;     // [B, ng] or unused
-  const uint32_t* vrank;     // [B, ng]
+  const uint32_t* vmask;     // [B, ngc] or unused
+  const uint32_t* vrank;     // [B, ngc]
   const _Float16* vrows;     // [L, B, H, n_s, 128]
   const _Float16* ktail;     // [B, H, cap, 128]
   const _Float16* vtail;
   const int32_t* tail_len;   // [B] or NULL
   float* part;               // [(nsplit+1), B, Hq, 130]
   int layer, B, H, Hq, rep, ng, n_a, n_n, n_s, krec_bytes, cap, nsplit, gps;
+  int ngc;                   // groups of capacity: stride of the per-head record arrays
   int split0;                // added to blockIdx.x (tail-only launches start at nsplit)
   float scale2;              // softmax scale * log2(e): scores live in the exp2 domain
 };

@@ -70,13 +70,13 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
     const int g = g_begin + it;
     if (!is_tail) {
       // ---- stage the two records
-      const u32x4* ks = reinterpret_cast<const u32x4*>(a.krec + (hd * a.ng + g) * (long long)a.krec_bytes);
-      const u32x4* vs = reinterpret_cast<const u32x4*>(a.vrec + (hd * a.ng + g) * (long long)VREC);
+      const u32x4* ks = reinterpret_cast<const u32x4*>(a.krec + (hd * a.ngc + g) * (long long)a.krec_bytes);
+      const u32x4* vs = reinterpret_cast<const u32x4*>(a.vrec + (hd * a.ngc + g) * (long long)VREC);
       if (tid < a.krec_bytes / 16) krec4[tid] = ks[tid];
       if (tid >= 128 && tid - 128 < VREC / 16) vrec4[tid - 128] = vs[tid - 128];
       if (a.n_s > 0) {
-        smask = a.vmask[(size_t)b * a.ng + g];
-        srank = a.vrank[(size_t)b * a.ng + g];
+        smask = a.vmask[(size_t)b * a.ngc + g];
+        srank = a.vrank[(size_t)b * a.ngc + g];
       }
       __syncthreads();
       // ---- Y[h][slot] = sum over normal channels of q * (+-s)
@@ -299,7 +299,7 @@ hipError_t launch_decode_attention(const Geom& g, int layer, float scale, const 
   const bool has_tail = cap > 0 && ktail && vtail && tail_len;
   a.tail_len = has_tail ? tail_len : nullptr;
   a.part = reinterpret_cast<float*>(ws);
-  a.layer = layer; a.B = g.B; a.H = g.H; a.Hq = g.Hq; a.rep = g.rep; a.ng = g.ng;
+  a.layer = layer; a.B = g.B; a.H = g.H; a.Hq = g.Hq; a.rep = g.rep; a.ng = g.ng; a.ngc = g.ngc;
   a.n_a = g.n_a; a.n_n = g.n_n; a.n_s = g.n_s; a.krec_bytes = g.krec; a.cap = cap;
   a.nsplit = attn_num_splits(g);
   a.scale2 = scale * 1.4426950408889634f;

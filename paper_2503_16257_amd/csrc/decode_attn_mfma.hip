@@ -140,8 +140,8 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a) {
   const int p_begin = split * a.gps;
   const int p_end = min(npairs, p_begin + a.gps);
 
-  const uint8_t* krec_base = a.krec + hd * a.ng * (long long)KREC;
-  const uint8_t* vrec_base = a.vrec + hd * a.ng * (long long)VREC;
+  const uint8_t* krec_base = a.krec + hd * a.ngc * (long long)KREC;
+  const uint8_t* vrec_base = a.vrec + hd * a.ngc * (long long)VREC;
 
   // prefetch registers: key record chunks and value words of both groups, value
   // scales of the group whose rows this lane owns in the PV tile (parity kb >> 1)
@@ -167,7 +167,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a) {
   auto load_masks = [&](int pp, uint32_t& s0, uint32_t& s1, uint32_t& rk) {
     s0 = s1 = rk = 0;
     if (HAS_SAL && pp < p_end) {
-      const size_t gi = (size_t)b * a.ng + 2 * pp;
+      const size_t gi = (size_t)b * a.ngc + 2 * pp;
       s0 = a.vmask[gi];
       rk = a.vrank[gi];
       if (2 * pp + 1 < a.ng) s1 = a.vmask[gi + 1];

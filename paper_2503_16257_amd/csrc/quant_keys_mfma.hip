@@ -67,6 +67,7 @@ template <int NA8T>
 __global__ __launch_bounds__(256) void k_encode_mfma_kernel(const u32x4* __restrict__ K,
                                                             const uint8_t* __restrict__ perm_g,
                                                             int T, int ng, int n_a_rt, int krec, int gpb,
+                                                            int ngc, int g_out0,
                                                             uint8_t* __restrict__ rec_out) {
   const int n_a = NA8T >= 0 ? 8 * NA8T : n_a_rt;
   const long long hd = blockIdx.y;
@@ -235,23 +236,25 @@ __global__ __launch_bounds__(256) void k_encode_mfma_kernel(const u32x4* __restr
       }
     }
     // ---- the finished record: LDS -> global, 16 bytes per lane
-    u32x4* dst = reinterpret_cast<u32x4*>(rec_out + (hd * ng + g) * (long long)krec);
+    u32x4* dst = reinterpret_cast<u32x4*>(rec_out + (hd * ngc + g_out0 + g) * (long long)krec);
     const int nch = krec >> 4;
     if (lane < nch) dst[lane] = recbuf[wave][lane];
     if (lane + 64 < nch) dst[lane + 64] = recbuf[wave][lane + 64];
   }
 }
 
-void launch_k_encode(const Geom& g, const void* K, uint8_t* packed, hipStream_t st) {
+void launch_k_encode(const Geom& g, const EncodeSpan& sp, const void* K, uint8_t* packed,
+                     hipStream_t st) {
   // two groups per wave: short-lived workgroups keep the memory system evenly loaded,
   // and the second group's load overlaps the first group's arithmetic
   const int gpb = 8;
-  dim3 grid((g.ng + gpb - 1) / gpb, (unsigned)g.nheads);
+  dim3 grid((sp.ng + gpb - 1) / gpb, (unsigned)sp.heads);
   const u32x4* k4 = reinterpret_cast<const u32x4*>(K);
-  const uint8_t* perm = packed + g.k_perm;
-  uint8_t* rec = packed + g.k_rec;
-#define VIDKV_ENC(N) \
-  hipLaunchKernelGGL(k_encode_mfma_kernel<N>, grid, dim3(256), 0, st, k4, perm, g.T, g.ng, g.n_a, g.krec, gpb, rec)
+  const uint8_t* perm = packed + g.k_perm + sp.head0 * D;
+  uint8_t* rec = packed + g.k_rec + (size_t)sp.head0 * g.ngc * g.krec;
+#define VIDKV_ENC(N)                                                                              \
+  hipLaunchKernelGGL(k_encode_mfma_kernel<N>, grid, dim3(256), 0, st, k4, perm, sp.in_tokens, sp.ng, \
+                     g.n_a, g.krec, gpb, g.ngc, sp.g_out0, rec)
   switch (g.n_a) {
     case 8:  VIDKV_ENC(1); break;
     case 16: VIDKV_ENC(2); break;

@@ -194,7 +194,7 @@ __device__ __forceinline__ void group_flags(const float* sc, const uint32_t* mk,
 template <bool FROM_MASK>
 __global__ __launch_bounds__(256) void v_sel_count_kernel(const float* __restrict__ scores,
                                                           const uint32_t* __restrict__ mask, int T,
-                                                          int ng, SelWs w) {
+                                                          int ng, int ngc, SelWs w) {
   const int b = blockIdx.y, slice = blockIdx.x, tid = threadIdx.x;
   __shared__ int sw[4];
   __shared__ int sres[2];
@@ -208,7 +208,7 @@ __global__ __launch_bounds__(256) void v_sel_count_kernel(const float* __restric
   }
   const int g = slice * (SEL_SLICE / G) + tid;
   uint32_t sel = 0, tie = 0;
-  if (g < ng) group_flags<FROM_MASK>(scores + (size_t)b * T, mask + (size_t)b * ng, g, kth, &sel, &tie);
+  if (g < ng) group_flags<FROM_MASK>(scores + (size_t)b * T, mask + (size_t)b * ngc, g, kth, &sel, &tie);
   int tot_s, tot_e;
   block_exscan_256(__popc(sel), sw, &tot_s);
   block_exscan_256(__popc(tie), sw, &tot_e);
@@ -220,7 +220,7 @@ __global__ __launch_bounds__(256) void v_sel_count_kernel(const float* __restric
 
 template <bool FROM_MASK>
 __global__ __launch_bounds__(256) void v_sel_mark_kernel(const float* __restrict__ scores, int T,
-                                                         int ng, int n_s, SelWs w,
+                                                         int ng, int ngc, int n_s, SelWs w,
                                                          int32_t* __restrict__ idx_out,
                                                          uint32_t* __restrict__ mask,
                                                          uint32_t* __restrict__ rank) {
@@ -242,7 +242,7 @@ __global__ __launch_bounds__(256) void v_sel_mark_kernel(const float* __restrict
     pre_s += ts;
     pre_e += te;
   }
-  uint32_t* mk = mask + (size_t)b * ng;
+  uint32_t* mk = mask + (size_t)b * ngc;
   if (g < ng) group_flags<FROM_MASK>(scores + (size_t)b * T, mk, g, kth, &sel, &tie);
   int tot;
   // ties: take those whose (global, index-ordered) tie number is below take_eq
@@ -261,7 +261,7 @@ __global__ __launch_bounds__(256) void v_sel_mark_kernel(const float* __restrict
                block_exscan_256(__popc(sel), sw, &tot);
   if (g < ng) {
     if (!FROM_MASK) mk[g] = sel;
-    rank[(size_t)b * ng + g] = (uint32_t)before;
+    rank[(size_t)b * ngc + g] = (uint32_t)before;
     int32_t* io = idx_out + (size_t)b * n_s;
     uint32_t s = sel;
     while (s) {
@@ -274,19 +274,42 @@ __global__ __launch_bounds__(256) void v_sel_mark_kernel(const float* __restrict
 }
 
 __global__ __launch_bounds__(256) void v_sel_scatter_kernel(const int32_t* __restrict__ idx_in,
-                                                            int n_s, int ng,
+                                                            int n_s, int ng, int ngc,
                                                             uint32_t* __restrict__ mask) {
   const int b = blockIdx.y;
   const int i = blockIdx.x * 256 + threadIdx.x;
   if (i < n_s) {
     const int t = idx_in[(size_t)b * n_s + i];
     if (t >= 0 && t < ng * G)                       // an index outside the cache is ignored
-      atomicOr(&mask[(size_t)b * ng + (t >> 5)], 1u << (t & 31));
+      atomicOr(&mask[(size_t)b * ngc + (t >> 5)], 1u << (t & 31));
   }
 }
 
 // The ternary coding pass (Eq. 6) lives in quant_values_enc.hip.
-void launch_v_encode(const Geom& g, float gamma, const void* V, uint8_t* packed, hipStream_t st);
+void launch_v_encode(const Geom& g, const EncodeSpan& sp, int n_s, float gamma, const void* V,
+                     uint8_t* packed, hipStream_t st);
+
+// MASK and RANK of groups appended behind the prefill tokens: none of their
+// tokens is protected, all n_s protected tokens lie before them.
+__global__ __launch_bounds__(256) void v_flush_marks_kernel(uint32_t* __restrict__ mask,
+                                                            uint32_t* __restrict__ rank, int B,
+                                                            int ngc, int g0, int n, uint32_t n_s) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < B * n) {
+    const size_t at = (size_t)(i / n) * ngc + g0 + (i % n);
+    mask[at] = 0;
+    rank[at] = n_s;
+  }
+}
+
+void launch_flush_marks(const Geom& g, int n_groups, uint8_t* packed, hipStream_t st) {
+  if (g.n_s == 0) return;
+  const int n = g.B * n_groups;
+  hipLaunchKernelGGL(v_flush_marks_kernel, dim3((n + 255) / 256), dim3(256), 0, st,
+                     reinterpret_cast<uint32_t*>(packed + g.v_mask),
+                     reinterpret_cast<uint32_t*>(packed + g.v_rank), g.B, g.ngc, g.ng, n_groups,
+                     (uint32_t)g.n_s);
+}
 
 size_t values_ws_bytes(const Geom& g) {
   const int nslice = (g.T + SEL_SLICE - 1) / SEL_SLICE;
@@ -304,7 +327,7 @@ hipError_t launch_quantize_values(const Geom& g, float gamma, const void* V, con
     const int nslice = (g.T + SEL_SLICE - 1) / SEL_SLICE;
     SelWs w = sel_ws(ws, g.B, nslice);
     const size_t n_hist = (size_t)g.B * 3 * SEL_BINS;
-    const size_t n_mask = (size_t)g.B * g.ng;
+    const size_t n_mask = (size_t)g.B * g.ngc;
     const size_t n_init = scores ? n_hist : n_mask;
     int32_t* idx_out = reinterpret_cast<int32_t*>(packed + g.v_idx);
     dim3 gs(nslice, g.B);
@@ -315,18 +338,19 @@ hipError_t launch_quantize_values(const Geom& g, float gamma, const void* V, con
       hipLaunchKernelGGL(v_sel_level_kernel<0>, gl, dim3(256), 0, st, scores, g.T, g.n_s, w);
       hipLaunchKernelGGL(v_sel_level_kernel<1>, gl, dim3(256), 0, st, scores, g.T, g.n_s, w);
       hipLaunchKernelGGL(v_sel_level_kernel<2>, gl, dim3(256), 0, st, scores, g.T, g.n_s, w);
-      hipLaunchKernelGGL(v_sel_count_kernel<false>, gs, dim3(256), 0, st, scores, mask, g.T, g.ng, w);
-      hipLaunchKernelGGL(v_sel_mark_kernel<false>, gs, dim3(256), 0, st, scores, g.T, g.ng, g.n_s,
+      hipLaunchKernelGGL(v_sel_count_kernel<false>, gs, dim3(256), 0, st, scores, mask, g.T, g.ng, g.ngc, w);
+      hipLaunchKernelGGL(v_sel_mark_kernel<false>, gs, dim3(256), 0, st, scores, g.T, g.ng, g.ngc, g.n_s,
                          w, idx_out, mask, rank);
     } else {
       hipLaunchKernelGGL(v_sel_scatter_kernel, dim3((g.n_s + 255) / 256, g.B), dim3(256), 0, st,
-                         idx, g.n_s, g.ng, mask);
-      hipLaunchKernelGGL(v_sel_count_kernel<true>, gs, dim3(256), 0, st, scores, mask, g.T, g.ng, w);
-      hipLaunchKernelGGL(v_sel_mark_kernel<true>, gs, dim3(256), 0, st, scores, g.T, g.ng, g.n_s, w,
+                         idx, g.n_s, g.ng, g.ngc, mask);
+      hipLaunchKernelGGL(v_sel_count_kernel<true>, gs, dim3(256), 0, st, scores, mask, g.T, g.ng, g.ngc, w);
+      hipLaunchKernelGGL(v_sel_mark_kernel<true>, gs, dim3(256), 0, st, scores, g.T, g.ng, g.ngc, g.n_s, w,
                          idx_out, mask, rank);
     }
   }
-  if (stages & 2u) launch_v_encode(g, gamma, V, packed, st);
+  if (stages & 2u)
+    launch_v_encode(g, EncodeSpan{g.T, g.ng, 0, g.nheads, 0}, g.n_s, gamma, V, packed, st);
   return hipGetLastError();
 }
 

@@ -28,7 +28,7 @@ __device__ __forceinline__ uint32_t pk_sub_u16(uint32_t a, uint32_t b) {
 
 __global__ __launch_bounds__(256) void v_encode_wave_kernel(const u32x4* __restrict__ V, int T,
                                                             int ng, int B, int H, int n_s,
-                                                            float gamma, int gpb,
+                                                            float gamma, int gpb, int ngc, int g_out0,
                                                             const uint32_t* __restrict__ mask,
                                                             const uint32_t* __restrict__ rank,
                                                             uint8_t* __restrict__ rec_out,
@@ -67,8 +67,8 @@ __global__ __launch_bounds__(256) void v_encode_wave_kernel(const u32x4* __restr
 
     uint32_t m = 0, r0 = 0;
     if (n_s > 0) {
-      m = __builtin_amdgcn_readfirstlane(mask[(size_t)b * ng + g]);
-      r0 = __builtin_amdgcn_readfirstlane(rank[(size_t)b * ng + g]);
+      m = __builtin_amdgcn_readfirstlane(mask[(size_t)b * ngc + g]);
+      r0 = __builtin_amdgcn_readfirstlane(rank[(size_t)b * ngc + g]);
     }
     // per slot pair: 1.0 / 0.0 halves for the sum, 0x8000 / 0 halves for the codes
     uint32_t keepf[4], keepm[4];
@@ -134,7 +134,7 @@ __global__ __launch_bounds__(256) void v_encode_wave_kernel(const u32x4* __restr
       words[mp] = word;
       sc16[mp] = h2_bits(h2{s16[0], s16[1]});
     }
-    uint8_t* rec = rec_out + (hd * ng + g) * (long long)VREC;
+    uint8_t* rec = rec_out + (hd * ngc + g_out0 + g) * (long long)VREC;
     u32x4 wv;
     wv[0] = words[0]; wv[1] = words[1]; wv[2] = words[2]; wv[3] = words[3];
     reinterpret_cast<u32x4*>(rec)[lane] = wv;                   // word (kb, x16, mp) at byte 16 lane + 4 mp
@@ -156,14 +156,17 @@ __global__ __launch_bounds__(256) void v_encode_wave_kernel(const u32x4* __restr
   }
 }
 
-void launch_v_encode(const Geom& g, float gamma, const void* V, uint8_t* packed, hipStream_t st) {
+// n_s = 0 codes every token (a flushed residual block has no protected tokens).
+void launch_v_encode(const Geom& g, const EncodeSpan& sp, int n_s, float gamma, const void* V,
+                     uint8_t* packed, hipStream_t st) {
   // one group per wave: many short-lived workgroups balance the memory system best here
   const int gpb = 4;
-  dim3 grid((g.ng + gpb - 1) / gpb, (unsigned)g.nheads);
+  dim3 grid((sp.ng + gpb - 1) / gpb, (unsigned)sp.heads);
   hipLaunchKernelGGL(v_encode_wave_kernel, grid, dim3(256), 0, st, reinterpret_cast<const u32x4*>(V),
-                     g.T, g.ng, g.B, g.H, g.n_s, gamma, gpb,
+                     sp.in_tokens, sp.ng, g.B, g.H, n_s, gamma, gpb, g.ngc, sp.g_out0,
                      reinterpret_cast<const uint32_t*>(packed + g.v_mask),
-                     reinterpret_cast<const uint32_t*>(packed + g.v_rank), packed + g.v_rec,
+                     reinterpret_cast<const uint32_t*>(packed + g.v_rank),
+                     packed + g.v_rec + (size_t)sp.head0 * g.ngc * VREC,
                      reinterpret_cast<u32x4*>(packed + g.v_rows));
 }
 

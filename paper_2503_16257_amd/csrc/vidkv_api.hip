@@ -14,6 +14,11 @@ hipError_t launch_decode_attention(const Geom& g, int layer, float scale, const 
                                    const void* vtail, int cap, const int32_t* tail_len, void* out,
                                    void* ws, unsigned stages, hipStream_t st);
 int attn_num_splits(const Geom& g);
+void launch_k_encode(const Geom& g, const EncodeSpan& sp, const void* K, uint8_t* packed,
+                     hipStream_t st);
+void launch_v_encode(const Geom& g, const EncodeSpan& sp, int n_s, float gamma, const void* V,
+                     uint8_t* packed, hipStream_t st);
+void launch_flush_marks(const Geom& g, int n_groups, uint8_t* packed, hipStream_t st);
 
 static size_t ws_keys(const Geom& g) {
   return align256((size_t)g.nheads * g.range_chunks * 2 * D * sizeof(_Float16)) + 256;
@@ -140,6 +145,32 @@ vidkv_status vidkv_decode_attention(const vidkv_params* p, int32_t layer, const 
                                     void* stream) {
   return vidkv_decode_attention_stages(p, layer, q, packed_K, packed_V, K_tail, V_tail,
                                        tail_capacity, tail_len, out, ws, ws_bytes, ~0u, stream);
+}
+
+vidkv_status vidkv_flush_residual(const vidkv_params* p, int32_t layer, const void* K_tail,
+                                  const void* V_tail, int32_t tail_capacity, int32_t n_flush,
+                                  void* packed_K, size_t packed_K_bytes, void* packed_V,
+                                  size_t packed_V_bytes, void* stream) {
+  Geom g;
+  if (!p || !K_tail || !V_tail || !packed_K || !packed_V) return VIDKV_EINVAL;
+  if (!make_geom(p, &g)) return VIDKV_ESHAPE;
+  if (layer < 0 || layer >= g.L) return VIDKV_EINVAL;
+  if (n_flush <= 0 || n_flush % G || tail_capacity < n_flush) return VIDKV_EINVAL;
+  if (g.T == 0) return VIDKV_EINVAL;               // no channel selection to code the keys with
+  if (!(p->gamma >= 0.0f) || !(p->gamma < 1e30f)) return VIDKV_EINVAL;
+  if ((long long)g.B * g.H > 65535) return VIDKV_ESHAPE;
+  if (!aligned(K_tail, 16) || !aligned(V_tail, 16) || !aligned(packed_K, 256) ||
+      !aligned(packed_V, 256))
+    return VIDKV_EINVAL;
+  if (g.T + n_flush > g.Tcap) return VIDKV_ENOSPACE;
+  if (packed_K_bytes < g.k_total || packed_V_bytes < g.v_total) return VIDKV_ENOSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const long long bh = (long long)g.B * g.H;
+  const EncodeSpan sp{tail_capacity, n_flush / G, g.ng, bh, layer * bh};
+  launch_k_encode(g, sp, K_tail, static_cast<uint8_t*>(packed_K), st);
+  launch_v_encode(g, sp, 0, p->gamma, V_tail, static_cast<uint8_t*>(packed_V), st);
+  launch_flush_marks(g, sp.ng, static_cast<uint8_t*>(packed_V), st);
+  return hipGetLastError() == hipSuccess ? VIDKV_OK : VIDKV_EHIP;
 }
 
 vidkv_status vidkv_calib_copy(void* dst, const void* src, size_t bytes, void* stream) {

@@ -44,6 +44,7 @@ union U4H {
 
 struct Geom {
   int L, B, H, Hq, rep, T, ng, n_a, n_n, n_s;
+  int Tcap, ngc;                   // capacity in tokens / groups: every per-head stride uses ngc
   long long nheads;                // L*B*H
   int krec;                        // bytes of one key record
   // key buffer
@@ -51,6 +52,16 @@ struct Geom {
   // value buffer
   size_t v_rec, v_idx, v_mask, v_rank, v_rows, v_total;
   int range_chunks;                // workgroups per head in the range pass
+};
+
+// Which heads and groups a coding launch covers: the whole tensor at prefill,
+// or one layer's residual block appended behind the groups already packed.
+struct EncodeSpan {
+  int in_tokens;      // tokens per head of the input tensor (its head stride)
+  int ng;             // groups to code, from input token 0 on
+  int g_out0;         // output group of input group 0
+  long long heads;    // heads covered by the launch
+  long long head0;    // first of them inside the packed buffer
 };
 
 __host__ __device__ inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
@@ -65,22 +76,24 @@ inline bool make_geom(const vidkv_params* p, Geom* g) {
   if (p->n_anom < 0 || p->n_anom > D || p->n_anom % 8) return false;
   if (p->use_fft != 1) return false;
   if (p->n_salient < 0 || p->n_salient > p->t_quant) return false;
+  if (p->t_capacity != 0 && (p->t_capacity < p->t_quant || p->t_capacity % G)) return false;
   g->L = p->n_layers; g->B = p->batch; g->H = p->n_kv_heads; g->Hq = p->n_q_heads;
   g->rep = g->Hq / g->H;
   g->T = p->t_quant; g->ng = g->T / G;
+  g->Tcap = p->t_capacity ? p->t_capacity : p->t_quant; g->ngc = g->Tcap / G;
   g->n_a = p->n_anom; g->n_n = D - g->n_a; g->n_s = p->n_salient;
   g->nheads = (long long)g->L * g->B * g->H;
   g->krec = 12 * g->n_a + 8 * g->n_n;
   g->k_perm = 0;
   g->k_rec = align256((size_t)g->nheads * D);
-  g->k_total = align256(g->k_rec + (size_t)g->nheads * g->ng * g->krec);
+  g->k_total = align256(g->k_rec + (size_t)g->nheads * g->ngc * g->krec);
   g->v_rec = 0;
-  size_t off = align256((size_t)g->nheads * g->ng * VREC);
+  size_t off = align256((size_t)g->nheads * g->ngc * VREC);
   g->v_idx = g->v_mask = g->v_rank = g->v_rows = off;
   if (g->n_s > 0) {
     g->v_idx = off;  off = align256(off + 4ull * g->B * g->n_s);
-    g->v_mask = off; off = align256(off + 4ull * g->B * g->ng);
-    g->v_rank = off; off = align256(off + 4ull * g->B * g->ng);
+    g->v_mask = off; off = align256(off + 4ull * g->B * g->ngc);
+    g->v_rank = off; off = align256(off + 4ull * g->B * g->ngc);
     g->v_rows = off; off = align256(off + 2ull * g->nheads * g->n_s * D);
   }
   g->v_total = off;

@@ -40,10 +40,13 @@ class GpuRun:
     """Device buffers of one workload pushed through the library."""
 
     def __init__(self, w: synth.Workload, device="cuda:0", gamma=GAMMA, K=None, V=None,
-                 saliency=None, salient_idx=None, quantize=True):
+                 saliency=None, salient_idx=None, quantize=True, t_capacity=0):
         self.w = w
         self.dev = device
-        self.p = vk.make_params(w.L, w.B, w.Hkv, w.Hq, w.T, w.n_anom, w.n_salient, gamma=gamma)
+        self.T = w.T                          # tokens packed so far (grows with flushes)
+        self.Tcap = t_capacity or w.T
+        self.p = vk.make_params(w.L, w.B, w.Hkv, w.Hq, w.T, w.n_anom, w.n_salient, gamma=gamma,
+                                t_capacity=t_capacity)
         self.K = torch.from_numpy(synth.keys(w)).to(device) if K is None else K
         self.V = torch.from_numpy(synth.values(w)).to(device) if V is None else V
         self.sal = None
@@ -81,6 +84,16 @@ class GpuRun:
             self._pv_np = self.pv.cpu().numpy()
         return self._pv_np
 
+    def flush(self, layer, K_tail, V_tail, cap, n_flush):
+        vk.flush_residual(self.p, layer, K_tail, V_tail, cap, n_flush, self.pk, self.pv)
+        torch.cuda.synchronize()
+        self._pk_np = self._pv_np = None
+
+    def advance(self, n_flush):
+        """After every layer has been flushed: the packed cache is n_flush tokens longer."""
+        self.T += n_flush
+        self.p.t_quant = self.T
+
     def attention(self, layer, q, K_tail=None, V_tail=None, cap=0, tail_len=None):
         out = torch.empty((self.w.B, self.w.Hq, 128), dtype=torch.float16, device=self.dev)
         out.fill_(float("nan"))
@@ -96,25 +109,25 @@ class GpuRun:
 
     def key_record(self, hd):
         w = self.w
-        sec = LY.key_sections(w.L, w.B, w.Hkv, w.T, w.n_anom)
+        sec = LY.key_sections(w.L, w.B, w.Hkv, self.Tcap, w.n_anom)
         rb = LY.key_record_bytes(w.n_anom)
-        ng = w.T // 32
+        ng, ngc = self.T // 32, self.Tcap // 32
         perm = self._bytes(self.pk, sec["perm"] + hd * 128, 128)
-        recs = self._bytes(self.pk, sec["rec"] + hd * ng * rb, ng * rb).reshape(ng, rb)
+        recs = self._bytes(self.pk, sec["rec"] + hd * ngc * rb, ng * rb).reshape(ng, rb)
         return LY.unpack_key_head(perm, recs, w.n_anom)
 
     def value_record(self, hd):
         w = self.w
-        ng = w.T // 32
-        recs = self._bytes(self.pv, hd * ng * LY.VREC, ng * LY.VREC).reshape(ng, LY.VREC)
+        ng, ngc = self.T // 32, self.Tcap // 32
+        recs = self._bytes(self.pv, hd * ngc * LY.VREC, ng * LY.VREC).reshape(ng, LY.VREC)
         codes, s16 = LY.unpack_value_head(recs)
         b = (hd // w.Hkv) % w.B
         n_s = w.n_salient
         if n_s:
-            sec = LY.value_sections(w.L, w.B, w.Hkv, w.T, n_s)
+            sec = LY.value_sections(w.L, w.B, w.Hkv, self.Tcap, n_s)
             idx = self._bytes(self.pv, sec["idx"] + 4 * b * n_s, 4 * n_s).view("<i4")
-            mask = self._bytes(self.pv, sec["mask"] + 4 * b * ng, 4 * ng).view("<u4")
-            rank = self._bytes(self.pv, sec["rank"] + 4 * b * ng, 4 * ng).view("<u4")
+            mask = self._bytes(self.pv, sec["mask"] + 4 * b * ngc, 4 * ng).view("<u4")
+            rank = self._bytes(self.pv, sec["rank"] + 4 * b * ngc, 4 * ng).view("<u4")
             rows = self._bytes(self.pv, sec["rows"] + 2 * hd * n_s * 128, 2 * n_s * 128) \
                 .view("<f2").reshape(n_s, 128)
         else:
@@ -189,7 +202,7 @@ def oracle_attention(run: GpuRun, layer: int, b: int, q_b: np.ndarray,
     Kd, Vd = [], []
     for h in range(w.Hkv):
         hd = (layer * w.B + b) * w.Hkv + h
-        if w.T:
+        if run.T:
             Kd.append(O.dequantize_keys_head(run.key_record(hd)))
             v = run.value_record(hd)
             Vd.append(O.ternary_dequant(v["codes"], v["s16"], v["idx"], v["rows"]))

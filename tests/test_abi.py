@@ -22,12 +22,12 @@ def _declared_functions():
 def test_library_exports_every_declared_symbol():
     names = _declared_functions()
     assert {"vidkv_quantize_keys", "vidkv_quantize_values", "vidkv_decode_attention",
-            "vidkv_packed_keys_bytes", "vidkv_packed_values_bytes", "vidkv_workspace_bytes",
+            "vidkv_flush_residual", "vidkv_packed_keys_bytes", "vidkv_packed_values_bytes", "vidkv_workspace_bytes",
             "vidkv_status_string", "vidkv_abi_version", "vidkv_calib_copy"} <= set(names)
     L = C.CDLL(vk.LIB_PATH)
     for n in names:
         assert hasattr(L, n), n
-    assert vk.abi_version() == 1
+    assert vk.abi_version() == 2
     assert vk.status_string(0) == "ok" and vk.status_string(3) == "buffer too small"
 
 
@@ -109,6 +109,26 @@ def test_entry_points_refuse_bad_arguments_before_launch():
     assert call(a11=vk.workspace_bytes(p, 2) - 1) == vk.ENOSPACE
     noscale = vk.make_params(1, 1, 4, 28, 64, 16, 4, softmax_scale=0.0)
     assert call(a0=C.byref(noscale)) == vk.EINVAL
+    # flush_residual: needs room behind t_quant, whole groups, an existing channel selection
+    roomy = vk.make_params(1, 1, 4, 28, 64, 16, 4, t_capacity=192)
+    rb = C.byref(roomy)
+    def flush(pp=rb, layer=0, K=A, V=A, cap=128, n=128, pk=A, pkb=big, pv=A, pvb=big):
+        return L.vidkv_flush_residual(pp, layer, K, V, cap, n, pk, pkb, pv, pvb, None)
+    assert flush(pp=None) == vk.EINVAL and flush(K=None) == vk.EINVAL and flush(pv=None) == vk.EINVAL
+    assert flush(layer=1) == vk.EINVAL
+    assert flush(n=0) == vk.EINVAL and flush(n=48) == vk.EINVAL and flush(cap=64) == vk.EINVAL
+    assert flush(pp=pb) == vk.ENOSPACE                                    # t_capacity == t_quant
+    assert flush(cap=256, n=160) == vk.ENOSPACE                           # 64 + 160 > 192
+    assert flush(pkb=vk.packed_keys_bytes(roomy) - 1) == vk.ENOSPACE
+    assert flush(pvb=vk.packed_values_bytes(roomy) - 1) == vk.ENOSPACE
+    empty = vk.make_params(1, 1, 4, 28, 0, 16, 0, t_capacity=128)
+    assert flush(pp=C.byref(empty)) == vk.EINVAL
+    assert vk.packed_keys_bytes(roomy) == LY.key_sections(1, 1, 4, 192, 16)["total"]
+    assert vk.packed_values_bytes(roomy) == LY.value_sections(1, 1, 4, 192, 4)["total"]
+    short = vk.make_params(1, 1, 4, 28, 64, 16, 4, t_capacity=32)
+    assert vk.packed_keys_bytes(short) == 0
+    odd = vk.make_params(1, 1, 4, 28, 64, 16, 4, t_capacity=100)
+    assert vk.packed_keys_bytes(odd) == 0
     # calib copy
     assert L.vidkv_calib_copy(None, A, 16, None) == vk.EINVAL
     assert L.vidkv_calib_copy(A, A, 8, None) == vk.EINVAL

@@ -384,3 +384,40 @@ def test_end_to_end_toy_quality():
     keep = np.ones(w.T, bool); keep[sal] = False
     Vd = V.astype(np.float64)
     assert ((Vd[keep] - Vr[keep]) ** 2).sum() / (Vd[keep] ** 2).sum() == pytest.approx(0.2775 - 0.01, abs=0.015)
+
+
+def test_flush_reading_block_local_and_idempotent():
+    """Residual flush (Alg. 1, Decoding).  The printed algorithm re-runs MixQuant
+    on the dequantized cache concatenated with the residual block; this build
+    codes only the block, with the prefill's channel split.  Two facts make the
+    two agree: (1) both codes are local to a 32-token group, so coding a block
+    alone gives what coding the whole sequence gives for those groups; (2)
+    re-coding already dequantized groups with the same split reproduces their
+    codes and sign bits, so leaving them untouched loses nothing - and it avoids
+    the one thing re-coding would change: the imaginary scale, a mean over 32
+    bins of which 2 are structurally zero, shrinks by 30/32 on every pass."""
+    w = synth.WORKLOADS["c1_toy_na8"]
+    K = synth.key_head(w, 0)[:512]
+    full = O.quantize_keys_head(K, 8)
+    blk = O.quantize_keys_block(K[384:512], full["anom"], full["norm"])      # last 4 groups alone
+    for k in ("a_codes", "a_s16", "a_z16", "n_bits", "n_sre16", "n_sim16"):
+        np.testing.assert_array_equal(blk[k], full[k][12:16], err_msg=k)
+    # (2) re-code the dequantized cache (rounded to the fp16 it would be held in)
+    Kd = O.dequantize_keys_head(full).astype(np.float16)
+    again = O.quantize_keys_block(Kd, full["anom"], full["norm"])
+    np.testing.assert_array_equal(again["a_codes"], full["a_codes"])
+    assert (again["n_bits"] != full["n_bits"]).mean() < 2e-3       # only coefficients lost in fp16 rounding
+    np.testing.assert_allclose(again["a_s16"].astype(np.float64), full["a_s16"].astype(np.float64), rtol=2e-3)
+    np.testing.assert_allclose(again["n_sre16"].astype(np.float64), full["n_sre16"].astype(np.float64), rtol=5e-3)
+    np.testing.assert_allclose(again["n_sim16"].astype(np.float64),
+                               full["n_sim16"].astype(np.float64) * 30 / 32, rtol=5e-3)
+    # values: a block without protected tokens is the plain 1.58Quant of Alg. 2
+    V = synth.value_head(w, 0)[:128]
+    none = np.zeros(0, dtype=np.int32)
+    qv = O.ternary_quant(V, none, 0.7)
+    s = np.abs(V.astype(np.float64)).reshape(4, 32, 128).mean(axis=1)          # [g, D]
+    np.testing.assert_array_equal(qv["s16"], s.astype(np.float16))
+    x = V.astype(np.float64).reshape(4, 32, 128).transpose(0, 2, 1)            # [g, D, G]
+    want = np.where(x > 0.7 * s[:, :, None], 1, np.where(x < -0.7 * s[:, :, None], -1, 0))
+    ok = ~qv["near"]
+    np.testing.assert_array_equal(qv["codes"][ok], want[ok])

@@ -22,6 +22,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+SAL_HIDDEN, SAL_N_TEXT = 3584, 32   # hidden size of the 7B models, text-query tokens
 BYTES_V_PER_ELEM = 0.2625      # 1.6-bit trits + one fp16 scale per 32 elements
 
 # HBM bytes per launch (read + written) from hardware counters: rocprofv3 --pmc
@@ -50,6 +51,8 @@ def algorithmic_bytes(w):
         "v_encode": 2.0 * N + v_packed + rows + (4.0 * w.B * w.T if w.n_salient else 0.0),
         "attn_partial": k_packed + v_packed + rows + tail + qo,
         "fp16_input": 2 * 2.0 * N,
+        # saliency scores (Eq. 7): visual and text hidden states once, scores out
+        "saliency": 2.0 * w.B * (w.T + SAL_N_TEXT) * SAL_HIDDEN + 4.0 * w.B * w.T,
     }
 
 
@@ -101,7 +104,7 @@ def main():
     ap.add_argument("--kernel-iters", type=int, default=20)
     ap.add_argument("--only", default=None,
                     choices=["k_range", "k_select", "k_encode", "v_select", "v_encode",
-                             "attn_partial", "attn_merge", "copy"],
+                             "attn_partial", "attn_merge", "copy", "saliency"],
                     help="profiling aid: after set-up run only this kernel --kernel-iters times "
                          "and exit without the JSON line")
     args = ap.parse_args()
@@ -149,6 +152,19 @@ def main():
         Vt = torch.from_numpy(np.stack(vt)).to(dev)
         tl = torch.full((w.B,), cap, dtype=torch.int32, device=dev)
 
+    # hidden states for the saliency scores (not part of the step: the scores are an input
+    # of quantize_values; timed alone).  1.4 GB at the long-video shape, far beyond the LLC.
+    Xv = Xt = None
+    if w.n_salient and w.B * w.T * SAL_HIDDEN * 2 < 8e9:
+        g = torch.Generator(device=dev); g.manual_seed(20250316)
+        Xv = torch.randn((w.B, w.T, SAL_HIDDEN), generator=g, device=dev, dtype=torch.float16)
+        Xt = torch.randn((w.B, SAL_N_TEXT, SAL_HIDDEN), generator=g, device=dev, dtype=torch.float16)
+        sal_out = torch.empty((w.B, w.T), dtype=torch.float32, device=dev)
+        sal_ws = vk.alloc_bytes(vk.saliency_workspace_bytes(w.B, SAL_HIDDEN), dev)
+
+    def saliency_scores(i):
+        vk.saliency_scores(Xv, Xt, sal_out, sal_ws)
+
     def q_keys(i, stages=None):
         vk.quantize_keys(p, Ks[i % NROT], pks[i % AROT], ws, stages=stages)
 
@@ -187,7 +203,8 @@ def main():
                "k_encode": lambda i: q_keys(i, 4), "v_select": lambda i: q_vals(i, 1),
                "v_encode": lambda i: q_vals(i, 2), "attn_partial": lambda i: attn(i, 1),
                "attn_merge": lambda i: attn(i, 2),
-               "copy": lambda i: vk.calib_copy(Vs[(i + 1) % NROT], Ks[i % NROT])}[args.only]
+               "copy": lambda i: vk.calib_copy(Vs[(i + 1) % NROT], Ks[i % NROT]),
+               "saliency": saliency_scores}[args.only]
         t = timed(sel, args.kernel_iters)
         print(f"{args.only}: {t * 1e6:.2f} us per call over {args.kernel_iters} calls", file=sys.stderr)
         return
@@ -214,6 +231,8 @@ def main():
         "attn_partial": timed(lambda i: attn(i, 1), it) / w.L,
         "attn_merge": timed(lambda i: attn(i, 2), it) / w.L,
     }
+    if Xv is not None:
+        kt["saliency"] = timed(saliency_scores, max(2, it // 4))
     t_qk = timed(lambda i: q_keys(i), it)
     t_qv = timed(lambda i: q_vals(i), it)
     t_at = timed(lambda i: attn(i), it)
@@ -229,6 +248,8 @@ def main():
 
     roofs = [roof("k_range"), roof("k_encode"), roof("v_encode"), roof("attn_partial", w.L)]
     dominant = max(roofs, key=lambda r: r["us"] * (w.L if r["kernel"] == "attn_partial" else 1))
+    if "saliency" in kt:                       # outside the step, listed for its own roofline
+        roofs.append(roof("saliency"))
     tokens = w.L * w.B * w.T
     res = {
         "metric": "visual tokens/s through quantize K + quantize V + 1 decode-attention step "

@@ -168,6 +168,23 @@ vidkv_status vidkv_flush_residual(const vidkv_params *params, int32_t layer,
                                   void *packed_V_dev, size_t packed_V_bytes,
                                   void *hip_stream);
 
+/* Sec. 3.3 (2), Eq. 7: the cross-modal score I(i, j) = X_v(i) . X_t(j) between
+ * visual token i and text token j, summed over the text tokens of the
+ * sequence: scores[b][i] = sum_j X_v[b][i] . X_t[b][j] (fp32 accumulation).
+ * The result is what vidkv_quantize_values takes as saliency_dev.  Which
+ * hidden states to pass (the paper does not say which layer) is the caller's
+ * choice.
+ *   X_v_dev   in : [B, n_visual, hidden_dim] fp16, 16-byte aligned
+ *   X_t_dev   in : [B, n_text, hidden_dim] fp16, n_text >= 1
+ *   hidden_dim   : multiple of 8, 8..16384
+ *   scores_dev out: [B, n_visual] float32
+ *   workspace_dev: >= vidkv_saliency_workspace_bytes(B, hidden_dim) bytes      */
+size_t vidkv_saliency_workspace_bytes(int32_t batch, int32_t hidden_dim);
+vidkv_status vidkv_saliency_scores(const void *X_v_dev, const void *X_t_dev, int32_t batch,
+                                   int32_t n_visual, int32_t n_text, int32_t hidden_dim,
+                                   float *scores_dev, void *workspace_dev,
+                                   size_t workspace_bytes, void *hip_stream);
+
 /* Measurement aids, not part of the method.  Each takes the arguments of the
  * entry point it is named after, checks them the same way, and launches only
  * the kernels selected by `stages`, so that a benchmark can bracket a single

@@ -229,6 +229,17 @@ def dequantize_keys_head(rec: dict) -> np.ndarray:
 # --------------------------------------------------------------------------
 # Values: token protection and the ternary quantizer (Eq. 6, Eq. 7; Alg. 2)
 # --------------------------------------------------------------------------
+def saliency_scores(Xv16: np.ndarray, Xt16: np.ndarray) -> np.ndarray:
+    """Eq. 7 (Sec. 3.3 (2)): I(i, j) = X_v(i) . X_t(j) for every visual token i
+    and text token j of one sequence; the paper does not say how the text axis
+    is reduced - here the scores of a visual token are summed over j.
+
+    Xv16 [Tv, d], Xt16 [Nt, d] fp16.  Returns [Tv] float64.
+    """
+    I = Xv16.astype(np.float64) @ Xt16.astype(np.float64).T        # [Tv, Nt]
+    return I.sum(axis=1)
+
+
 def select_salient_tokens(scores: np.ndarray, n_s: int) -> np.ndarray:
     """Top-n_s tokens by saliency score (Sec. 3.3 (2): top n = p * l_v tokens).
 

@@ -58,6 +58,10 @@ def lib() -> C.CDLL:
         L.vidkv_quantize_values.restype = C.c_int
         L.vidkv_flush_residual.argtypes = [PP, i32, vp, vp, i32, i32, vp, sz, vp, sz, vp]
         L.vidkv_flush_residual.restype = C.c_int
+        L.vidkv_saliency_workspace_bytes.argtypes = [i32, i32]
+        L.vidkv_saliency_workspace_bytes.restype = sz
+        L.vidkv_saliency_scores.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, sz, vp]
+        L.vidkv_saliency_scores.restype = C.c_int
         L.vidkv_decode_attention.argtypes = [PP, i32, vp, vp, vp, vp, vp, i32, vp, vp, vp, sz, vp]
         L.vidkv_decode_attention.restype = C.c_int
         u32 = C.c_uint32
@@ -189,6 +193,21 @@ def flush_residual(p: VidkvParams, layer: int, K_tail, V_tail, tail_capacity: in
         tail_capacity, n_flush, _ptr(packed_K, torch.uint8, "packed_K"), _nbytes(packed_K),
         _ptr(packed_V, torch.uint8, "packed_V"), _nbytes(packed_V), _stream(stream)),
         "vidkv_flush_residual")
+
+
+def saliency_workspace_bytes(batch: int, hidden_dim: int) -> int:
+    return lib().vidkv_saliency_workspace_bytes(batch, hidden_dim)
+
+
+def saliency_scores(X_v, X_t, scores, workspace, stream=None) -> None:
+    """vidkv_saliency_scores: X_v [B,Tv,d] fp16, X_t [B,Nt,d] fp16 -> scores [B,Tv] f32."""
+    import torch
+    B, Tv, d = X_v.shape
+    assert X_t.shape[0] == B and X_t.shape[2] == d and tuple(scores.shape) == (B, Tv)
+    _check(lib().vidkv_saliency_scores(
+        _ptr(X_v, torch.float16, "X_v"), _ptr(X_t, torch.float16, "X_t"), B, Tv, X_t.shape[1], d,
+        _ptr(scores, torch.float32, "scores"), _ptr(workspace, torch.uint8, "workspace"),
+        _nbytes(workspace), _stream(stream)), "vidkv_saliency_scores")
 
 
 def calib_copy(dst, src, stream=None) -> None:

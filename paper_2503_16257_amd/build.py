@@ -11,8 +11,8 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libvidkv.so")
 
-SOURCES = ["vidkv_api.hip", "quant_keys.hip", "quant_keys_mfma.hip", "quant_values.hip", "quant_values_enc.hip", "decode_attn.hip",
-           "decode_attn_mfma.hip"]
+SOURCES = ["vidkv_api.hip", "quant_keys.hip", "quant_keys_mfma.hip", "quant_values.hip",
+           "quant_values_enc.hip", "decode_attn.hip", "decode_attn_mfma.hip", "saliency.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     # packed-fp32 VALU forms are kept off for all device code

@@ -19,6 +19,8 @@ void launch_k_encode(const Geom& g, const EncodeSpan& sp, const void* K, uint8_t
 void launch_v_encode(const Geom& g, const EncodeSpan& sp, int n_s, float gamma, const void* V,
                      uint8_t* packed, hipStream_t st);
 void launch_flush_marks(const Geom& g, int n_groups, uint8_t* packed, hipStream_t st);
+hipError_t launch_saliency(const void* Xv, const void* Xt, int B, int Tv, int Nt, int d,
+                           float* scores, float* tsum, hipStream_t st);
 
 static size_t ws_keys(const Geom& g) {
   return align256((size_t)g.nheads * g.range_chunks * 2 * D * sizeof(_Float16)) + 256;
@@ -171,6 +173,26 @@ vidkv_status vidkv_flush_residual(const vidkv_params* p, int32_t layer, const vo
   launch_v_encode(g, sp, 0, p->gamma, V_tail, static_cast<uint8_t*>(packed_V), st);
   launch_flush_marks(g, sp.ng, static_cast<uint8_t*>(packed_V), st);
   return hipGetLastError() == hipSuccess ? VIDKV_OK : VIDKV_EHIP;
+}
+
+size_t vidkv_saliency_workspace_bytes(int32_t batch, int32_t hidden_dim) {
+  if (batch < 1 || hidden_dim < 8) return 0;
+  return align256((size_t)batch * hidden_dim * sizeof(float));
+}
+
+vidkv_status vidkv_saliency_scores(const void* X_v, const void* X_t, int32_t batch,
+                                   int32_t n_visual, int32_t n_text, int32_t hidden_dim,
+                                   float* scores, void* ws, size_t ws_bytes, void* stream) {
+  if (!X_t || !ws) return VIDKV_EINVAL;
+  if (batch < 1 || n_visual < 0 || n_text < 1) return VIDKV_EINVAL;
+  if (n_visual > 0 && (!X_v || !scores)) return VIDKV_EINVAL;
+  if (hidden_dim < 8 || hidden_dim % 8 || hidden_dim > 16384 || batch > 65535) return VIDKV_ESHAPE;
+  if (!aligned(X_v, 16) || !aligned(X_t, 2) || !aligned(scores, 4) || !aligned(ws, 256))
+    return VIDKV_EINVAL;
+  if (ws_bytes < vidkv_saliency_workspace_bytes(batch, hidden_dim)) return VIDKV_ENOSPACE;
+  const hipError_t e = launch_saliency(X_v, X_t, batch, n_visual, n_text, hidden_dim, scores,
+                                       static_cast<float*>(ws), static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? VIDKV_OK : VIDKV_EHIP;
 }
 
 vidkv_status vidkv_calib_copy(void* dst, const void* src, size_t bytes, void* stream) {

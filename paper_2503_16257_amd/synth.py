@@ -27,7 +27,7 @@ TOK_PER_FRAME = 196
 BASE_SEED = 20250316
 
 # tensor ids (part of the seed)
-T_K, T_V, T_Q, T_SAL, T_TAIL, T_OUTL, T_STEP = 0, 1, 2, 3, 4, 5, 10
+T_K, T_V, T_Q, T_SAL, T_TAIL, T_OUTL, T_HID, T_STEP = 0, 1, 2, 3, 4, 5, 6, 10
 
 
 @dataclass(frozen=True)
@@ -166,6 +166,26 @@ def saliency(w: Workload) -> np.ndarray:
     """Cross-modal saliency scores per visual token: [B, T] float32 ~ U(0, 1)."""
     r = _rng(w, T_SAL)
     return r.random((w.B, w.T), dtype=np.float32)
+
+
+HIDDEN_DIM = 3584        # hidden size of the 7B models the paper runs
+N_TEXT = 32              # text-query tokens of a prompt
+
+
+def hidden_states(w: Workload, b: int, rows: int | None = None, d: int = HIDDEN_DIM,
+                  n_text: int = N_TEXT):
+    """Hidden states of sequence b for the saliency scores: visual [rows, d] and
+    text [n_text, d] fp16 ~ N(0, 1), the text rows sharing a common direction with
+    a fifth of the visual rows so that the scores are not pure noise."""
+    rows = w.T if rows is None else rows
+    r = _rng(w, T_HID, b)
+    Xt = r.standard_normal((n_text, d), dtype=np.float32)
+    topic = r.standard_normal(d, dtype=np.float32)
+    Xt += 0.5 * topic
+    Xv = r.standard_normal((rows, d), dtype=np.float32)
+    hit = r.random(rows) < 0.2
+    Xv[hit] += 0.3 * topic
+    return _to_f16(Xv), _to_f16(Xt)
 
 
 def keys(w: Workload) -> np.ndarray:

@@ -22,7 +22,7 @@ def _declared_functions():
 def test_library_exports_every_declared_symbol():
     names = _declared_functions()
     assert {"vidkv_quantize_keys", "vidkv_quantize_values", "vidkv_decode_attention",
-            "vidkv_flush_residual", "vidkv_packed_keys_bytes", "vidkv_packed_values_bytes", "vidkv_workspace_bytes",
+            "vidkv_flush_residual", "vidkv_saliency_scores", "vidkv_packed_keys_bytes", "vidkv_packed_values_bytes", "vidkv_workspace_bytes",
             "vidkv_status_string", "vidkv_abi_version", "vidkv_calib_copy"} <= set(names)
     L = C.CDLL(vk.LIB_PATH)
     for n in names:
@@ -129,6 +129,16 @@ def test_entry_points_refuse_bad_arguments_before_launch():
     assert vk.packed_keys_bytes(short) == 0
     odd = vk.make_params(1, 1, 4, 28, 64, 16, 4, t_capacity=100)
     assert vk.packed_keys_bytes(odd) == 0
+    # saliency scores
+    def sal(Xv=A, Xt=A, B=1, Tv=64, Nt=4, d=3584, sc=A, ws=A, wsb=big):
+        return L.vidkv_saliency_scores(Xv, Xt, B, Tv, Nt, d, sc, ws, wsb, None)
+    assert sal(Xt=None) == vk.EINVAL and sal(sc=None) == vk.EINVAL and sal(Xv=None) == vk.EINVAL
+    assert sal(Nt=0) == vk.EINVAL and sal(B=0) == vk.EINVAL and sal(Tv=-1) == vk.EINVAL
+    assert sal(d=100) == vk.ESHAPE and sal(d=0) == vk.ESHAPE and sal(d=32768) == vk.ESHAPE
+    assert sal(Xv=A + 8) == vk.EINVAL
+    assert vk.saliency_workspace_bytes(2, 3584) == 2 * 3584 * 4
+    assert sal(B=2, wsb=2 * 3584 * 4 - 1) == vk.ENOSPACE
+    assert vk.saliency_workspace_bytes(0, 3584) == 0
     # calib copy
     assert L.vidkv_calib_copy(None, A, 16, None) == vk.EINVAL
     assert L.vidkv_calib_copy(A, A, 8, None) == vk.EINVAL

@@ -421,3 +421,31 @@ def test_flush_reading_block_local_and_idempotent():
     want = np.where(x > 0.7 * s[:, :, None], 1, np.where(x < -0.7 * s[:, :, None], -1, 0))
     ok = ~qv["near"]
     np.testing.assert_array_equal(qv["codes"][ok], want[ok])
+
+
+def test_saliency_scores_brute_force_and_linearity():
+    """Eq. 7 summed over the text tokens: brute-force double loop on a tiny case,
+    linearity in the text rows (the sum of per-text-token scores), and the
+    equivalent matrix-vector form X_v . (sum_j X_t(j))."""
+    rng = np.random.default_rng(21)
+    Xv = _f16(rng.standard_normal((7, 24))); Xt = _f16(rng.standard_normal((3, 24)))
+    got = O.saliency_scores(Xv, Xt)
+    want = np.zeros(7)
+    for i in range(7):
+        for j in range(3):
+            for c in range(24):
+                want[i] += float(Xv[i, c]) * float(Xt[j, c])
+    np.testing.assert_allclose(got, want, rtol=0, atol=1e-12)
+    per_j = sum(O.saliency_scores(Xv, Xt[j:j + 1]) for j in range(3))
+    np.testing.assert_allclose(got, per_j, atol=1e-12)
+    np.testing.assert_allclose(got, Xv.astype(np.float64) @ Xt.astype(np.float64).sum(axis=0), atol=1e-12)
+    # a visual token orthogonal to every text token scores 0; one equal to the only text token scores |x|^2
+    e = np.zeros((2, 24), np.float16); e[0, 0] = 2.0; e[1, 1] = 3.0
+    t = np.zeros((1, 24), np.float16); t[0, 1] = 3.0
+    np.testing.assert_array_equal(O.saliency_scores(e, t), [0.0, 9.0])
+    # the synthetic hidden states plant a common direction: those visual tokens rank on top
+    w = synth.WORKLOADS["c1_toy"]
+    Xv, Xt = synth.hidden_states(w, 0, rows=512, d=256)
+    s = O.saliency_scores(Xv, Xt)
+    top = np.argsort(-s)[:50]
+    assert s[top].min() > np.median(s) + 3 * s.std() / 4

@@ -74,6 +74,12 @@ typedef struct vidkv_params {
                             for this many tokens so that vidkv_flush_residual
                             can append blocks in place; every call on the same
                             buffers must pass the same t_capacity              */
+  int32_t salient_bits;  /* how the protected value tokens are kept.  0 or 16:
+                            verbatim fp16 rows.  2: Alg. 2's STPQuant - the
+                            protected rows of a head, gathered in token order,
+                            are coded with Eq. 4 at 2 bits per channel over
+                            groups of 32 protected tokens (the last group may
+                            be shorter)                                        */
 } vidkv_params;
 
 /* Size queries: pure host functions, usable without a GPU.  Return 0 when

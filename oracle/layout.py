@@ -42,7 +42,10 @@ Value buffer
   section IDX    : int32  [B][n_s]   protected token indices, ascending
   section MASK   : uint32 [B][T/32]  bit (t % 32) of word t/32 = token t protected
   section RANK   : uint32 [B][T/32]  number of protected tokens before group g
-  section ROWS   : fp16   [L][B][H][n_s][128]  the protected rows verbatim
+  section ROWS   : fp16   [L][B][H][n_s][128]  the protected rows verbatim; or, with 2-bit
+                   protected rows, [L][B][H][ceil(n_s/32)] records of 1536 bytes:
+                   uint8 [32 rows][32]  codes, channel 4 j + r of a row in bits 2r, 2r+1 of byte j
+                   fp16  [128] s, fp16 [128] z   (Eq. 4 per channel over the record's rows)
   (IDX..ROWS are absent when n_s = 0.)
 """
 from __future__ import annotations
@@ -52,6 +55,7 @@ import numpy as np
 G = 32
 D = 128
 VREC = 1280
+PREC = 1536
 
 
 def _align(x: int, a: int = 256) -> int:
@@ -69,7 +73,7 @@ def key_sections(L: int, B: int, H: int, T: int, n_a: int) -> dict:
     return {"perm": 0, "rec": off_rec, "total": _align(total)}
 
 
-def value_sections(L: int, B: int, H: int, T: int, n_s: int) -> dict:
+def value_sections(L: int, B: int, H: int, T: int, n_s: int, sal_bits: int = 16) -> dict:
     nh = L * B * H
     ng = T // G
     off = _align(nh * ng * VREC)
@@ -82,7 +86,8 @@ def value_sections(L: int, B: int, H: int, T: int, n_s: int) -> dict:
         sec["rank"] = off
         off = _align(off + 4 * B * ng)
         sec["rows"] = off
-        off = _align(off + 2 * nh * n_s * D)
+        rows = nh * ((n_s + G - 1) // G) * PREC if sal_bits == 2 else 2 * nh * n_s * D
+        off = _align(off + rows)
     sec["total"] = off
     return sec
 
@@ -239,3 +244,30 @@ def unpack_salient(buf: np.ndarray, sec: dict, b: int, T: int, n_s: int):
 def salient_rows(buf: np.ndarray, sec: dict, hd: int, n_s: int) -> np.ndarray:
     o = sec["rows"] + 2 * hd * n_s * D
     return np.ascontiguousarray(buf[o:o + 2 * n_s * D]).view("<f2").reshape(n_s, D)
+
+
+def pack_protected2(codes: np.ndarray, s16: np.ndarray, z16: np.ndarray) -> np.ndarray:
+    """2-bit protected rows of one head -> uint8 [npg * 1536].  codes [n_s, D] in 0..3,
+    s16 / z16 [npg, D] fp16."""
+    n_s = codes.shape[0]
+    npg = (n_s + G - 1) // G
+    out = np.zeros((npg, PREC), dtype=np.uint8)
+    full = np.zeros((npg * G, D), dtype=np.uint8)
+    full[:n_s] = codes
+    q = full.reshape(npg, G, D // 4, 4).astype(np.uint32)
+    by = (q[..., 0] | (q[..., 1] << 2) | (q[..., 2] << 4) | (q[..., 3] << 6)).astype(np.uint8)
+    out[:, :1024] = by.reshape(npg, 1024)
+    out[:, 1024:1280] = np.ascontiguousarray(s16.astype("<f2")).view(np.uint8).reshape(npg, 256)
+    out[:, 1280:1536] = np.ascontiguousarray(z16.astype("<f2")).view(np.uint8).reshape(npg, 256)
+    return out.reshape(-1)
+
+
+def unpack_protected2(buf: np.ndarray, n_s: int):
+    """Inverse of pack_protected2 for one head's records -> (codes [n_s, D], s16, z16 [npg, D])."""
+    npg = (n_s + G - 1) // G
+    r = np.ascontiguousarray(buf[:npg * PREC]).reshape(npg, PREC)
+    by = r[:, :1024].reshape(npg, G, D // 4)
+    codes = np.stack([(by >> (2 * k)) & 3 for k in range(4)], axis=-1).reshape(npg * G, D)[:n_s]
+    s16 = np.ascontiguousarray(r[:, 1024:1280]).view("<f2").reshape(npg, D)
+    z16 = np.ascontiguousarray(r[:, 1280:1536]).view("<f2").reshape(npg, D)
+    return codes.astype(np.uint8), s16, z16

@@ -283,9 +283,49 @@ def ternary_quant(V16: np.ndarray, salient_idx: np.ndarray, gamma: float):
     }
 
 
+def stp_quant_rows(rows16: np.ndarray, bits: int = 2) -> dict:
+    """Alg. 2, STPQuant, the protected branch: GQuant(X[E], d = channel, bit = 2).
+
+    rows16 [n_s, D] fp16: the protected rows of one head gathered in token
+    order.  Eq. 4 per channel over groups of G consecutive protected rows; the
+    last group holds n_s mod G rows when that is not zero and takes its minimum
+    and maximum over the rows it has.  Returns codes [n_s, D] uint8, s16 and z16
+    [ceil(n_s / G), D] fp16, near [n_s, D] bool.
+    """
+    n_s, D = rows16.shape
+    npg = (n_s + G - 1) // G
+    levels = (1 << bits) - 1
+    codes = np.zeros((n_s, D), dtype=np.uint8)
+    near = np.zeros((n_s, D), dtype=bool)
+    s_all = np.zeros((npg, D)); z_all = np.zeros((npg, D))
+    for pg in range(npg):
+        x = rows16[pg * G:(pg + 1) * G].astype(np.float64)          # [n <= G, D]
+        z = x.min(axis=0)
+        s = (x.max(axis=0) - z) / levels
+        safe = np.where(s > 0, s, 1.0)
+        u = (x - z) / safe
+        c = np.clip(np.rint(u), 0, levels)
+        nr = np.abs(u - (np.floor(u) + 0.5)) < BAND
+        c[:, s == 0] = 0
+        nr[:, s == 0] = False
+        codes[pg * G:(pg + 1) * G] = c.astype(np.uint8)
+        near[pg * G:(pg + 1) * G] = nr
+        s_all[pg] = s; z_all[pg] = z
+    return {"codes": codes, "s16": s_all.astype(np.float16), "z16": z_all.astype(np.float16), "near": near}
+
+
+def stp_dequant_rows(codes: np.ndarray, s16: np.ndarray, z16: np.ndarray) -> np.ndarray:
+    """Eq. 4, right half, for the protected rows: X' = Q * s + z with the group's stored
+    fp16 s, z.  -> [n_s, D] float64."""
+    n_s = codes.shape[0]
+    pg = np.arange(n_s) // G
+    return codes.astype(np.float64) * s16.astype(np.float64)[pg] + z16.astype(np.float64)[pg]
+
+
 def ternary_dequant(codes: np.ndarray, s16: np.ndarray, salient_idx: np.ndarray,
                     rows16: np.ndarray) -> np.ndarray:
-    """V' = s * code for coded tokens, the verbatim fp16 row for protected ones. -> [T, D]."""
+    """V' = s * code for coded tokens; protected tokens take the rows given (the verbatim
+    fp16 rows, or the dequantized 2-bit rows of STPQuant). -> [T, D]."""
     x = codes.astype(np.float64) * s16.astype(np.float64)[..., None]        # [g, c, t]
     g, c, t = x.shape
     out = x.transpose(0, 2, 1).reshape(g * t, c)

@@ -172,7 +172,8 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
       while (sm) {
         const int t = __ffs(sm) - 1;
         sm &= sm - 1;
-        const float v = (float)a.vrows[(hd * a.n_s + r) * D + c_o];
+        const float v = a.sal_bits == 2 ? protected2_value(a, hd, r, c_o)
+                                        : (float)a.vrows[(hd * a.n_s + r) * D + c_o];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
           const int h = half_o + 2 * i;
@@ -301,6 +302,7 @@ hipError_t launch_decode_attention(const Geom& g, int layer, float scale, const 
   a.part = reinterpret_cast<float*>(ws);
   a.layer = layer; a.B = g.B; a.H = g.H; a.Hq = g.Hq; a.rep = g.rep; a.ng = g.ng; a.ngc = g.ngc;
   a.n_a = g.n_a; a.n_n = g.n_n; a.n_s = g.n_s; a.krec_bytes = g.krec; a.cap = cap;
+  a.sal_bits = g.sal_bits; a.npg = g.npg;
   a.nsplit = attn_num_splits(g);
   a.scale2 = scale * 1.4426950408889634f;
   a.split0 = 0;

@@ -45,7 +45,8 @@ __device__ __forceinline__ float swap_max16(float v) {
   return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
 }
 
-template <int NA8, bool HAS_SAL>
+// SAL: 0 no protected tokens, 1 protected rows in fp16, 2 protected rows as 2-bit records
+template <int NA8, int SAL>
 __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a) {
   constexpr int NA = 8 * NA8, NN = D - NA;
   constexpr int NB = NN / 8;                 // normal 8-channel blocks
@@ -166,23 +167,34 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a) {
   uint32_t sm0c = 0, sm1c = 0, rkc = 0, sm0n = 0, sm1n = 0, rkn = 0;
   auto load_masks = [&](int pp, uint32_t& s0, uint32_t& s1, uint32_t& rk) {
     s0 = s1 = rk = 0;
-    if (HAS_SAL && pp < p_end) {
+    if ((SAL != 0) && pp < p_end) {
       const size_t gi = (size_t)b * a.ngc + 2 * pp;
       s0 = a.vmask[gi];
       rk = a.vrank[gi];
       if (2 * pp + 1 < a.ng) s1 = a.vmask[gi + 1];
     }
   };
+  // what a lane keeps of protected row r: its two channels 2 lane, 2 lane + 1 as an fp16
+  // pair, or (2-bit records) the byte that holds their codes
+  auto row_word = [&](uint32_t r) -> uint32_t {
+    if (SAL == 2) {
+      const uint8_t* rec = reinterpret_cast<const uint8_t*>(a.vrows) + (hd * a.npg + (r >> 5)) * (long long)PREC;
+      return rec[(r & 31) * 32 + (lane >> 1)];
+    }
+    return *(reinterpret_cast<const uint32_t*>(a.vrows + (hd * a.n_s + r) * D) + lane);
+  };
   auto issue_rows = [&](uint32_t s0, uint32_t s1, uint32_t rk, uint32_t* rows) {
     const int cnt = __popc(s0) + __popc(s1);
-    const uint32_t* base = reinterpret_cast<const uint32_t*>(a.vrows + (hd * a.n_s + rk) * D) + lane;
 #pragma unroll
     for (int j = 0; j < NROW; ++j)
-      if (j < cnt) rows[j] = base[j * (D / 2)];
+      if (j < cnt) rows[j] = row_word(rk + j);
   };
+  // scale and zero point (Eq. 4) of my two channels in the current group of protected rows
+  int sal_pg = -1;
+  float sal_s0 = 0.f, sal_s1 = 0.f, sal_z0 = 0.f, sal_z1 = 0.f;
   int p = p_begin + wave;
   if (p < p_end) prefetch(p);
-  if (HAS_SAL) {
+  if ((SAL != 0)) {
     load_masks(p, sm0c, sm1c, rkc);
     load_masks(p + 4, sm0n, sm1n, rkn);
     if (sm0c | sm1c) issue_rows(sm0c, sm1c, rkc, rowcur);
@@ -202,7 +214,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a) {
     sv.q = vspre;
     if (p + 4 < p_end) prefetch(p + 4);
     uint32_t sm0f = 0, sm1f = 0, rkf = 0;        // masks of the pair after the next one
-    if (HAS_SAL) {
+    if ((SAL != 0)) {
       if (sm0n | sm1n) issue_rows(sm0n, sm1n, rkn, rownext);
       load_masks(p + 8, sm0f, sm1f, rkf);
     }
@@ -341,7 +353,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a) {
       for (int m = 0; m < 8; ++m)
 #pragma unroll
         for (int i = 0; i < 4; ++i) o[m][i] *= ar[i];
-      if (HAS_SAL) {
+      if ((SAL != 0)) {
 #pragma unroll
         for (int h = 0; h < 8; ++h) {
           const float ah = al16[wave][h];
@@ -382,16 +394,31 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a) {
       for (int i = 0; i < 4; ++i) o[m][i] = fmaf(sc, C[i], o[m][i]);
     }
     // ---- protected tokens: fp16 rows (prefetched) weighted by the probabilities
-    if (HAS_SAL) {
+    if ((SAL != 0)) {
       if (sm0c | sm1c) {
 #pragma unroll
         for (int i = 0; i < 8; ++i) pl[wave][slot_token(kb, i)][x16] = pr[i];
         unsigned long long sm = (unsigned long long)sm0c | ((unsigned long long)sm1c << 32);
-        auto add_row = [&](uint32_t bits) {
+        auto add_row = [&](uint32_t bits, uint32_t r) {
           const int t64 = __ffsll((long long)sm) - 1;      // bit t of parity t64 >> 5
           sm &= sm - 1;
-          const h2 v = bits_h2(bits);
-          const float v0 = (float)v[0], v1 = (float)v[1];
+          float v0, v1;
+          if (SAL == 2) {
+            if ((int)(r >> 5) != sal_pg) {
+              sal_pg = (int)(r >> 5);
+              const uint8_t* rec = reinterpret_cast<const uint8_t*>(a.vrows) + (hd * a.npg + sal_pg) * (long long)PREC;
+              const h2 s2 = bits_h2(reinterpret_cast<const uint32_t*>(rec + 1024)[lane]);
+              const h2 z2 = bits_h2(reinterpret_cast<const uint32_t*>(rec + 1280)[lane]);
+              sal_s0 = (float)s2[0]; sal_s1 = (float)s2[1];
+              sal_z0 = (float)z2[0]; sal_z1 = (float)z2[1];
+            }
+            const uint32_t nib = bits >> (4 * (lane & 1));
+            v0 = fmaf((float)(nib & 3u), sal_s0, sal_z0);
+            v1 = fmaf((float)((nib >> 2) & 3u), sal_s1, sal_z1);
+          } else {
+            const h2 v = bits_h2(bits);
+            v0 = (float)v[0]; v1 = (float)v[1];
+          }
           const float* pp = &pl[wave][t64 & 31][8 * (t64 >> 5)];
 #pragma unroll
           for (int h = 0; h < 8; ++h) {
@@ -402,10 +429,10 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a) {
         };
 #pragma unroll
         for (int j = 0; j < NROW; ++j)
-          if (sm) add_row(rowcur[j]);
+          if (sm) add_row(rowcur[j], rkc + j);
         uint32_t rk = rkc + NROW;                           // more than NROW rows: fetch on demand
         while (sm) {
-          add_row(*(reinterpret_cast<const uint32_t*>(a.vrows + (hd * a.n_s + rk) * D) + lane));
+          add_row(row_word(rk), rk);
           ++rk;
         }
       }
@@ -433,7 +460,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a) {
       for (int i = 0; i < 4; ++i) ow[wave][4 * kb + i][16 * m + x16] = 0.5f * o[m][i];
   }
   if (kb == 0 && par == 0) { mw[wave][hcol] = m_run; lw[wave][hcol] = l_run; }
-  if (HAS_SAL) {
+  if ((SAL != 0)) {
     // same wave, LDS operations complete in order: add the fp16-row part
 #pragma unroll
     for (int h = 0; h < 8; ++h) {
@@ -474,8 +501,9 @@ bool attn_mfma_supported(int n_a) {
 
 template <int NA8>
 static void launch_one(const AttnArgs& a, dim3 grid, hipStream_t st) {
-  if (a.n_s > 0) hipLaunchKernelGGL((attn_mfma_kernel<NA8, true>), grid, dim3(256), 0, st, a);
-  else           hipLaunchKernelGGL((attn_mfma_kernel<NA8, false>), grid, dim3(256), 0, st, a);
+  if (a.n_s > 0 && a.sal_bits == 2) hipLaunchKernelGGL((attn_mfma_kernel<NA8, 2>), grid, dim3(256), 0, st, a);
+  else if (a.n_s > 0) hipLaunchKernelGGL((attn_mfma_kernel<NA8, 1>), grid, dim3(256), 0, st, a);
+  else hipLaunchKernelGGL((attn_mfma_kernel<NA8, 0>), grid, dim3(256), 0, st, a);
 }
 
 void launch_attn_mfma(const AttnArgs& a, dim3 grid, hipStream_t st) {

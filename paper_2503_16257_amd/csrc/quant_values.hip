@@ -289,6 +289,53 @@ __global__ __launch_bounds__(256) void v_sel_scatter_kernel(const int32_t* __res
 void launch_v_encode(const Geom& g, const EncodeSpan& sp, int n_s, float gamma, const void* V,
                      uint8_t* packed, hipStream_t st);
 
+// Alg. 2, STPQuant, protected branch: the protected rows of one head, gathered
+// in token order, coded with Eq. 4 at 2 bits per channel over groups of 32
+// protected tokens (the last group may hold fewer).  grid (npg, nheads), block
+// 128: thread = channel.  Record: codes [32 rows][32 bytes] (channel 4 j + r of
+// a row in bits 2r.. of byte j), fp16 s[128], fp16 z[128].
+__global__ __launch_bounds__(128) void v_protect2_kernel(const _Float16* __restrict__ V, int T,
+                                                         int B, int H, int n_s, int npg,
+                                                         const int32_t* __restrict__ idx,
+                                                         uint8_t* __restrict__ out) {
+  const int pg = blockIdx.x, c = threadIdx.x;
+  const long long hd = blockIdx.y;
+  const int b = (int)((hd / H) % B);
+  const int cnt = min(G, n_s - pg * G);
+  __shared__ int tok[G];
+  __shared__ uint8_t code_s[G][D];
+  if (c < G) tok[c] = c < cnt ? idx[(size_t)b * n_s + pg * G + c] : 0;
+  __syncthreads();
+  const _Float16* head = V + hd * (long long)T * D;
+  float x[G];
+  float lo = 65504.0f, hi = -65504.0f;
+#pragma unroll
+  for (int r = 0; r < G; ++r) {
+    x[r] = r < cnt ? (float)head[(size_t)tok[r] * D + c] : 0.0f;
+    if (r < cnt) { lo = fminf(lo, x[r]); hi = fmaxf(hi, x[r]); }
+  }
+  const float rng = hi - lo;
+  const float inv = rng > 0.0f ? 3.0f / rng : 0.0f;
+#pragma unroll
+  for (int r = 0; r < G; ++r) {
+    float u = (x[r] - lo) * inv;
+    u = fminf(fmaxf(rintf(u), 0.0f), 3.0f);
+    code_s[r][c] = r < cnt ? (uint8_t)u : (uint8_t)0;
+  }
+  uint8_t* rec = out + (hd * npg + pg) * (long long)PREC;
+  reinterpret_cast<_Float16*>(rec + 1024)[c] = (_Float16)(rng / 3.0f);
+  reinterpret_cast<_Float16*>(rec + 1280)[c] = (_Float16)lo;
+  __syncthreads();
+  // 256 dwords of codes: dword w = row w / 8, channels 16 (w % 8) ..
+  for (int w = c; w < 256; w += 128) {
+    const int r = w >> 3, c0 = 16 * (w & 7);
+    uint32_t v = 0;
+#pragma unroll
+    for (int k = 0; k < 16; ++k) v |= (uint32_t)code_s[r][c0 + k] << (2 * k);
+    reinterpret_cast<uint32_t*>(rec)[w] = v;
+  }
+}
+
 // MASK and RANK of groups appended behind the prefill tokens: none of their
 // tokens is protected, all n_s protected tokens lie before them.
 __global__ __launch_bounds__(256) void v_flush_marks_kernel(uint32_t* __restrict__ mask,
@@ -349,8 +396,13 @@ hipError_t launch_quantize_values(const Geom& g, float gamma, const void* V, con
                          idx_out, mask, rank);
     }
   }
-  if (stages & 2u)
+  if (stages & 2u) {
     launch_v_encode(g, EncodeSpan{g.T, g.ng, 0, g.nheads, 0}, g.n_s, gamma, V, packed, st);
+    if (g.n_s > 0 && g.sal_bits == 2)
+      hipLaunchKernelGGL(v_protect2_kernel, dim3(g.npg, (unsigned)g.nheads), dim3(128), 0, st,
+                         reinterpret_cast<const _Float16*>(V), g.T, g.B, g.H, g.n_s, g.npg,
+                         reinterpret_cast<const int32_t*>(packed + g.v_idx), packed + g.v_rows);
+  }
   return hipGetLastError();
 }
 

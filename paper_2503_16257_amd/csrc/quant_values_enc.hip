@@ -143,8 +143,9 @@ __global__ __launch_bounds__(256) void v_encode_wave_kernel(const u32x4* __restr
       sv[0] = sc16[0]; sv[1] = sc16[1]; sv[2] = sc16[2]; sv[3] = sc16[3];
       reinterpret_cast<u32x4*>(rec + 1024)[x16] = sv;           // fp16 [r = x16][m]
     }
-    // protected rows, verbatim, to ROWS[rank + order inside the group]
-    uint32_t w = m, r = r0;
+    // protected rows, verbatim, to ROWS[rank + order inside the group] (not when they are
+    // kept at 2 bits: a pass of its own codes them)
+    uint32_t w = rows_out ? m : 0u, r = r0;
     while (w) {
       const int t = __ffs(w) - 1;
       w &= w - 1;
@@ -167,7 +168,7 @@ void launch_v_encode(const Geom& g, const EncodeSpan& sp, int n_s, float gamma, 
                      reinterpret_cast<const uint32_t*>(packed + g.v_mask),
                      reinterpret_cast<const uint32_t*>(packed + g.v_rank),
                      packed + g.v_rec + (size_t)sp.head0 * g.ngc * VREC,
-                     reinterpret_cast<u32x4*>(packed + g.v_rows));
+                     g.sal_bits == 16 ? reinterpret_cast<u32x4*>(packed + g.v_rows) : nullptr);
 }
 
 }  // namespace vidkv

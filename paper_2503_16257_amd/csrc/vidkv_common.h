@@ -29,6 +29,7 @@ namespace vidkv {
 constexpr int D = 128;
 constexpr int G = 32;
 constexpr int VREC = 1280;         // bytes of one value record
+constexpr int PREC = 1536;         // bytes of one record of 32 protected rows at 2 bits (Eq. 4)
 constexpr int RANGE_CHUNK = 512;   // tokens per workgroup in the key range pass
 constexpr int MAX_REP = 8;         // query heads per KV head
 
@@ -45,6 +46,7 @@ union U4H {
 struct Geom {
   int L, B, H, Hq, rep, T, ng, n_a, n_n, n_s;
   int Tcap, ngc;                   // capacity in tokens / groups: every per-head stride uses ngc
+  int sal_bits, npg;               // protected rows: 16 = fp16, 2 = Eq. 4 records; groups of 32 rows
   long long nheads;                // L*B*H
   int krec;                        // bytes of one key record
   // key buffer
@@ -77,11 +79,14 @@ inline bool make_geom(const vidkv_params* p, Geom* g) {
   if (p->use_fft != 1) return false;
   if (p->n_salient < 0 || p->n_salient > p->t_quant) return false;
   if (p->t_capacity != 0 && (p->t_capacity < p->t_quant || p->t_capacity % G)) return false;
+  if (p->salient_bits != 0 && p->salient_bits != 16 && p->salient_bits != 2) return false;
   g->L = p->n_layers; g->B = p->batch; g->H = p->n_kv_heads; g->Hq = p->n_q_heads;
   g->rep = g->Hq / g->H;
   g->T = p->t_quant; g->ng = g->T / G;
   g->Tcap = p->t_capacity ? p->t_capacity : p->t_quant; g->ngc = g->Tcap / G;
   g->n_a = p->n_anom; g->n_n = D - g->n_a; g->n_s = p->n_salient;
+  g->sal_bits = p->salient_bits == 2 ? 2 : 16;
+  g->npg = (g->n_s + G - 1) / G;
   g->nheads = (long long)g->L * g->B * g->H;
   g->krec = 12 * g->n_a + 8 * g->n_n;
   g->k_perm = 0;
@@ -94,7 +99,9 @@ inline bool make_geom(const vidkv_params* p, Geom* g) {
     g->v_idx = off;  off = align256(off + 4ull * g->B * g->n_s);
     g->v_mask = off; off = align256(off + 4ull * g->B * g->ngc);
     g->v_rank = off; off = align256(off + 4ull * g->B * g->ngc);
-    g->v_rows = off; off = align256(off + 2ull * g->nheads * g->n_s * D);
+    g->v_rows = off;
+    off = align256(off + (g->sal_bits == 2 ? (size_t)g->nheads * g->npg * PREC
+                                           : 2ull * g->nheads * g->n_s * D));
   }
   g->v_total = off;
   g->range_chunks = (g->T + RANGE_CHUNK - 1) / RANGE_CHUNK;

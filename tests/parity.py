@@ -40,13 +40,14 @@ class GpuRun:
     """Device buffers of one workload pushed through the library."""
 
     def __init__(self, w: synth.Workload, device="cuda:0", gamma=GAMMA, K=None, V=None,
-                 saliency=None, salient_idx=None, quantize=True, t_capacity=0):
+                 saliency=None, salient_idx=None, quantize=True, t_capacity=0, salient_bits=0):
         self.w = w
         self.dev = device
         self.T = w.T                          # tokens packed so far (grows with flushes)
         self.Tcap = t_capacity or w.T
         self.p = vk.make_params(w.L, w.B, w.Hkv, w.Hq, w.T, w.n_anom, w.n_salient, gamma=gamma,
-                                t_capacity=t_capacity)
+                                t_capacity=t_capacity, salient_bits=salient_bits)
+        self.sal_bits = 2 if salient_bits == 2 else 16
         self.K = torch.from_numpy(synth.keys(w)).to(device) if K is None else K
         self.V = torch.from_numpy(synth.values(w)).to(device) if V is None else V
         self.sal = None
@@ -124,10 +125,17 @@ class GpuRun:
         b = (hd // w.Hkv) % w.B
         n_s = w.n_salient
         if n_s:
-            sec = LY.value_sections(w.L, w.B, w.Hkv, self.Tcap, n_s)
+            sec = LY.value_sections(w.L, w.B, w.Hkv, self.Tcap, n_s, self.sal_bits)
             idx = self._bytes(self.pv, sec["idx"] + 4 * b * n_s, 4 * n_s).view("<i4")
             mask = self._bytes(self.pv, sec["mask"] + 4 * b * ngc, 4 * ng).view("<u4")
             rank = self._bytes(self.pv, sec["rank"] + 4 * b * ngc, 4 * ng).view("<u4")
+            if self.sal_bits == 2:
+                npg = (n_s + 31) // 32
+                raw = self._bytes(self.pv, sec["rows"] + hd * npg * LY.PREC, npg * LY.PREC)
+                pc, ps, pz = LY.unpack_protected2(raw, n_s)
+                return {"codes": codes, "s16": s16, "idx": idx, "mask": mask, "rank": rank,
+                        "p_codes": pc, "p_s16": ps, "p_z16": pz,
+                        "rows": O.stp_dequant_rows(pc, ps, pz)}
             rows = self._bytes(self.pv, sec["rows"] + 2 * hd * n_s * 128, 2 * n_s * 128) \
                 .view("<f2").reshape(n_s, 128)
         else:
@@ -186,7 +194,15 @@ def check_values_head(run: GpuRun, hd: int, V_head: np.ndarray, sal_idx: np.ndar
         _, m_ref, r_ref = LY.unpack_salient(tmp, small, 0, w.T, w.n_salient)
         np.testing.assert_array_equal(got["mask"], m_ref)
         np.testing.assert_array_equal(got["rank"], r_ref)
-        np.testing.assert_array_equal(got["rows"].view(np.uint16), ref["rows"].view(np.uint16))
+        if run.sal_bits == 2:
+            pref = O.stp_quant_rows(ref["rows"])
+            bad = (got["p_codes"] != pref["codes"]) & ~pref["near"]
+            assert not bad.any(), f"protected 2-bit codes differ at {np.argwhere(bad)[:5]} head {hd}"
+            _count(stats, "v2bit", pref["near"].sum(), pref["near"].size)
+            np.testing.assert_array_equal(got["p_z16"].view(np.uint16), pref["z16"].view(np.uint16))
+            assert ulp_diff_f16(got["p_s16"], pref["s16"]) <= 1
+        else:
+            np.testing.assert_array_equal(got["rows"].view(np.uint16), ref["rows"].view(np.uint16))
         assert not got["codes"][:, :, :].transpose(0, 2, 1).reshape(w.T, 128)[sal_idx].any()
 
 

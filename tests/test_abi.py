@@ -125,6 +125,11 @@ def test_entry_points_refuse_bad_arguments_before_launch():
     assert flush(pp=C.byref(empty)) == vk.EINVAL
     assert vk.packed_keys_bytes(roomy) == LY.key_sections(1, 1, 4, 192, 16)["total"]
     assert vk.packed_values_bytes(roomy) == LY.value_sections(1, 1, 4, 192, 4)["total"]
+    two = vk.make_params(1, 2, 4, 28, 640, 16, 70, salient_bits=2)
+    assert vk.packed_values_bytes(two) == LY.value_sections(1, 2, 4, 640, 70, 2)["total"]
+    assert vk.packed_values_bytes(vk.make_params(1, 2, 4, 28, 640, 16, 70, salient_bits=16)) == \
+        LY.value_sections(1, 2, 4, 640, 70)["total"]
+    assert vk.packed_values_bytes(vk.make_params(1, 2, 4, 28, 640, 16, 70, salient_bits=4)) == 0
     short = vk.make_params(1, 1, 4, 28, 64, 16, 4, t_capacity=32)
     assert vk.packed_keys_bytes(short) == 0
     odd = vk.make_params(1, 1, 4, 28, 64, 16, 4, t_capacity=100)

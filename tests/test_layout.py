@@ -147,3 +147,26 @@ def test_sections_and_salient_round_trip():
     np.testing.assert_array_equal(i2, idx)
     assert mask[0] == (1 | (1 << 31)) and mask[1] == 0b11 and mask[3] == (1 << 4 | 1 << 5 | 1 << 6)
     assert rank.tolist() == [0, 2, 4, 4, 7, 7, 7, 8]
+
+
+def test_protected_rows_two_bit_records_roundtrip_and_size():
+    rng = np.random.default_rng(8)
+    for n_s in (1, 31, 32, 70, 96):
+        npg = (n_s + 31) // 32
+        codes = rng.integers(0, 4, (n_s, 128)).astype(np.uint8)
+        s16 = rng.random((npg, 128)).astype(np.float16)
+        z16 = rng.standard_normal((npg, 128)).astype(np.float16)
+        buf = LY.pack_protected2(codes, s16, z16)
+        assert buf.size == npg * LY.PREC
+        c, s, z = LY.unpack_protected2(buf, n_s)
+        np.testing.assert_array_equal(c, codes)
+        np.testing.assert_array_equal(s.view(np.uint16), s16.view(np.uint16))
+        np.testing.assert_array_equal(z.view(np.uint16), z16.view(np.uint16))
+    # byte j of a row: channel 4 j + r in bits 2r, 2r + 1
+    codes = np.zeros((1, 128), np.uint8); codes[0, 6] = 3; codes[0, 127] = 1
+    buf = LY.pack_protected2(codes, np.zeros((1, 128), np.float16), np.zeros((1, 128), np.float16))
+    assert buf[1] == 3 << 4 and buf[31] == 1 << 6 and buf[:1024].sum() == (3 << 4) + (1 << 6)
+    a = LY.value_sections(1, 2, 4, 640, 70)
+    b = LY.value_sections(1, 2, 4, 640, 70, 2)
+    assert a["rows"] == b["rows"]
+    assert b["total"] - b["rows"] == (8 * 3 * LY.PREC + 255) // 256 * 256

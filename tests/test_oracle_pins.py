@@ -449,3 +449,40 @@ def test_saliency_scores_brute_force_and_linearity():
     s = O.saliency_scores(Xv, Xt)
     top = np.argsort(-s)[:50]
     assert s[top].min() > np.median(s) + 3 * s.std() / 4
+
+
+def test_stp_rows_two_bit_brute_force_and_bounds():
+    """STPQuant's protected branch (Alg. 2): Eq. 4 at 2 bits per channel over groups of 32
+    gathered rows, ragged last group.  Brute force on a tiny case, exactness on four-level
+    data, the half-step error bound, and agreement with the key-side Eq. 4 coder on whole groups."""
+    rng = np.random.default_rng(31)
+    rows = _f16(rng.standard_normal((70, 128)) * 3)
+    q = O.stp_quant_rows(rows)
+    assert q["codes"].shape == (70, 128) and q["s16"].shape == (3, 128)
+    for pg, c in ((0, 5), (1, 77), (2, 127)):                      # group 2 holds 6 rows
+        col = [float(v) for v in rows[32 * pg:32 * (pg + 1), c]]
+        lo, hi = min(col), max(col)
+        s = (hi - lo) / 3
+        want = [min(3, max(0, round((v - lo) / s))) for v in col]   # Python rounds half to even
+        ok = ~q["near"][32 * pg:32 * (pg + 1), c]
+        assert [w for w, k in zip(want, ok) if k] == [int(v) for v, k in zip(q["codes"][32 * pg:32 * (pg + 1), c], ok) if k]
+        assert float(q["z16"][pg, c]) == lo and float(q["s16"][pg, c]) == float(np.float16(s))
+    d = O.stp_dequant_rows(q["codes"], q["s16"], q["z16"])
+    pg = np.arange(70) // 32
+    step = q["s16"].astype(np.float64)[pg]
+    assert np.all(np.abs(d - rows.astype(np.float64)) <= 0.5 * step * (1 + 2e-3) + 3 * step * 2 ** -11)
+    # rows that take exactly four equally spaced values per channel come back exactly
+    lv = _f16(np.array([-1.5, -0.5, 0.5, 1.5]))
+    four = lv[rng.integers(0, 4, (64, 128))]
+    four[0] = lv[0]; four[1] = lv[3]; four[32] = lv[0]; four[33] = lv[3]
+    q4 = O.stp_quant_rows(four)
+    np.testing.assert_array_equal(O.stp_dequant_rows(q4["codes"], q4["s16"], q4["z16"]), four.astype(np.float64))
+    # whole groups: the same arithmetic as the key-side group quantizer
+    g = O.gquant(rows[:64], bits=2)
+    np.testing.assert_array_equal(q["codes"][:64].reshape(2, 32, 128).transpose(0, 2, 1), g["codes"])
+    np.testing.assert_array_equal(q["s16"][:2], g["s16"])
+    # a constant channel: s = 0, codes 0, value restored from z
+    const = rows.copy(); const[:, 3] = np.float16(2.5)
+    qc = O.stp_quant_rows(const)
+    assert not qc["codes"][:, 3].any() and np.all(qc["s16"][:, 3] == 0)
+    assert np.all(O.stp_dequant_rows(qc["codes"], qc["s16"], qc["z16"])[:, 3] == 2.5)

@@ -101,6 +101,11 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="c4_long")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--no-fft", action="store_true",
+                    help="code the normal key channels with the non-FFT 1-bit quantizer (Eq. 4, n = 1) "
+                         "instead of Eq. 5; not the headline configuration")
+    ap.add_argument("--salient-bits", type=int, default=16, choices=[16, 2],
+                    help="protected value tokens as fp16 rows (default) or at 2 bits (Alg. 2, STPQuant)")
     ap.add_argument("--kernel-iters", type=int, default=20)
     ap.add_argument("--only", default=None,
                     choices=["k_range", "k_select", "k_encode", "v_select", "v_encode",
@@ -122,7 +127,8 @@ def main():
     dev = "cuda:0"
     w = synth.WORKLOADS[args.workload]
     p = vk.make_params(w.L, w.B, w.Hkv, w.Hq, w.T, w.n_anom, w.n_salient,
-                       gamma=float(np.float32(0.7)))
+                       gamma=float(np.float32(0.7)), use_fft=0 if args.no_fft else 1,
+                       salient_bits=args.salient_bits)
 
     # ---- inputs, resident in HBM.  NROT independent copies are rotated so that
     # a step never finds its inputs in the 256 MB last-level cache.
@@ -260,7 +266,9 @@ def main():
         "data": "synthetic",
         "config": {"workload": w.name, "layers": w.L, "batch": w.B, "kv_heads": w.Hkv,
                    "q_heads": w.Hq, "t_quant": w.T, "t_tail": w.T_tail, "n_anom": w.n_anom,
-                   "n_salient": w.n_salient, "input_rotation": NROT, "cache_rotation": AROT},
+                   "n_salient": w.n_salient, "input_rotation": NROT, "cache_rotation": AROT,
+                   "key_normal_channels": "1-bit without FFT (Eq. 4)" if args.no_fft else "FFT 1-bit (Eq. 5)",
+                   "protected_rows": "2-bit (Eq. 4)" if args.salient_bits == 2 else "fp16"},
         "quantize_GBps_fp16_input": round(ab["fp16_input"] / (t_qk + t_qv) / 1e9, 1),
         "quantize_ms": {"keys": round(t_qk * 1e3, 4), "values": round(t_qv * 1e3, 4)},
         "decode_attn_visual_tokens_per_s": round(tokens / t_at, 1),

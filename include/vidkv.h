@@ -64,7 +64,9 @@ typedef struct vidkv_params {
   int32_t t_quant;       /* Tq >= 0, multiple of 32: tokens held in packed form */
   int32_t n_anom;        /* 2-bit key channels per head: 0..128, multiple of 8
                             (k * D of Sec. 3.2 (1))                             */
-  int32_t use_fft;       /* must be 1: Eq. 5 path for the normal channels       */
+  int32_t use_fft;       /* normal key channels: 1 = FFT-based 1-bit quantizer
+                            (Eq. 5), 0 = Eq. 4 at 1 bit on the tokens themselves
+                            (the paper's "standard" 1-bit, Sec. 4.1)            */
   int32_t n_salient;     /* protected value tokens per sequence, 0..Tq
                             (n = p * l_v of Sec. 3.3 (2))                       */
   float gamma;           /* ternary threshold factor of Eq. 6 (paper: 0.7)      */
@@ -138,7 +140,8 @@ vidkv_status vidkv_quantize_values(const vidkv_params *params, const void *V_dev
  *                     layer; may be NULL when tail_capacity == 0
  *   tail_len_dev in : [B] int32, each 0..tail_capacity; NULL means all zero
  *   out_dev     out : [B, Hq, 128] fp16 (fp32 accumulation, RNE at the end)
- *   workspace_dev   : >= vidkv_workspace_bytes(params, 2) bytes
+ *   workspace_dev   : >= vidkv_workspace_bytes(params, 2) bytes (the size
+ *                     depends on t_capacity, not on t_quant)
  * With Tq == 0 this is plain attention over the residual tokens; a sequence
  * with no token at all gets zeros.                                            */
 vidkv_status vidkv_decode_attention(const vidkv_params *params, int32_t layer,

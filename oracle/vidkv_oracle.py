@@ -186,9 +186,14 @@ def fft1bit_dequant(bits: np.ndarray, sre16: np.ndarray, sim16: np.ndarray) -> n
 # --------------------------------------------------------------------------
 # Keys: MixQuant (Alg. 3) = selection + 2-bit anomalous + FFT 1-bit normal
 # --------------------------------------------------------------------------
-def quantize_keys_block(K16: np.ndarray, anom: np.ndarray, norm: np.ndarray) -> dict:
+def quantize_keys_block(K16: np.ndarray, anom: np.ndarray, norm: np.ndarray,
+                        use_fft: bool = True) -> dict:
     """The group coding of Alg. 3 for [T, D] tokens with a GIVEN channel split:
-    Eq. 4 at 2 bits on the anomalous channels, Eq. 5 on the others.
+    Eq. 4 at 2 bits on the anomalous channels; on the others Eq. 5 (1BitQuant
+    with the FFT), or with use_fft = False the "standard" 1-bit quantizer of
+    Sec. 4.1, which is Alg. 3's GQuant(bit = 1) applied to the tokens
+    themselves: Eq. 4 with n = 1 (z = min, s = max - min, code in {0, 1}).  In
+    that case n_bits holds the codes by token and n_sre16 / n_sim16 hold s / z.
 
     This is also the residual flush of Alg. 1 (Decoding, the branch taken when
     the residual buffer holds R tokens) under this build's reading: the block
@@ -196,19 +201,24 @@ def quantize_keys_block(K16: np.ndarray, anom: np.ndarray, norm: np.ndarray) -> 
     codes are local to a 32-token group, so earlier groups are not affected.
     """
     a = gquant(K16[:, anom], bits=2)
-    n = fft1bit_quant(K16[:, norm])
+    if use_fft:
+        n = fft1bit_quant(K16[:, norm])
+    else:
+        n1 = gquant(K16[:, norm], bits=1)
+        n = {"bits": n1["codes"], "sre16": n1["s16"], "sim16": n1["z16"], "near": n1["near"]}
     return {
         "anom": anom, "norm": norm, "perm": np.concatenate([anom, norm]).astype(np.int64),
         "a_codes": a["codes"], "a_s16": a["s16"], "a_z16": a["z16"], "a_near": a["near"],
         "n_bits": n["bits"], "n_sre16": n["sre16"], "n_sim16": n["sim16"], "n_near": n["near"],
+        "fft": use_fft,
     }
 
 
-def quantize_keys_head(K16: np.ndarray, n_a: int):
+def quantize_keys_head(K16: np.ndarray, n_a: int, use_fft: bool = True):
     """Alg. 3 for one [T, D] head.  Returns the logical (unpacked) cache record."""
     R = key_channel_range(K16)
     anom, norm, perm = select_anomalous_channels(R, n_a)
-    rec = quantize_keys_block(K16, anom, norm)
+    rec = quantize_keys_block(K16, anom, norm, use_fft)
     rec["range"] = R
     rec["perm"] = perm
     return rec
@@ -222,7 +232,10 @@ def dequantize_keys_head(rec: dict) -> np.ndarray:
     if len(anom):
         out[:, anom] = gdequant(rec["a_codes"], rec["a_s16"], rec["a_z16"])
     if len(norm):
-        out[:, norm] = fft1bit_dequant(rec["n_bits"], rec["n_sre16"], rec["n_sim16"])
+        if rec.get("fft", True):
+            out[:, norm] = fft1bit_dequant(rec["n_bits"], rec["n_sre16"], rec["n_sim16"])
+        else:
+            out[:, norm] = gdequant(rec["n_bits"], rec["n_sre16"], rec["n_sim16"])
     return out
 
 

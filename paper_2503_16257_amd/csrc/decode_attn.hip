@@ -87,9 +87,15 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
         for (int i = 0; i < a.n_n; ++i) {
           const int blk = i >> 3, e = i & 7;
           const uint32_t w = kbits[blk * 16 + k];
-          const float sgn = ((w >> (8 * hi + e)) & 1u) ? 1.0f : -1.0f;
-          const float s = (float)krec16[6 * a.n_a + 2 * a.n_n + (blk * 2 + use_im) * 8 + e];
-          y += qp[h_s][a.n_a + i] * (s * sgn);
+          const uint32_t bit = (w >> (8 * hi + e)) & 1u;
+          const _Float16* meta = krec16 + 6 * a.n_a + 2 * a.n_n + blk * 16;
+          float val;
+          if (a.use_fft) {
+            val = bit ? (float)meta[use_im * 8 + e] : -(float)meta[use_im * 8 + e];
+          } else {
+            val = fmaf((float)bit, (float)meta[e], (float)meta[8 + e]);
+          }
+          y += qp[h_s][a.n_a + i] * val;
         }
         Y[h_s][slot] = y;
       }
@@ -97,14 +103,19 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
       // ---- score[h][t]: inverse real DFT of Y plus the 2-bit channels
       if (h_s < R) {
         const int t = t_s;
-        float v = Y[h_s][0] + ((t & 1) ? -Y[h_s][16] : Y[h_s][16]);
-        float w2 = 0.0f;
+        float v;
+        if (a.use_fft) {
+          v = Y[h_s][0] + ((t & 1) ? -Y[h_s][16] : Y[h_s][16]);
+          float w2 = 0.0f;
 #pragma unroll
-        for (int k = 1; k < 16; ++k) {
-          const int ph = (k * t) & 31;
-          w2 += Y[h_s][k] * cs[ph] - Y[h_s][16 + k] * sn[ph];
+          for (int k = 1; k < 16; ++k) {
+            const int ph = (k * t) & 31;
+            w2 += Y[h_s][k] * cs[ph] - Y[h_s][16 + k] * sn[ph];
+          }
+          v = (v + 2.0f * w2) * (1.0f / 32.0f);
+        } else {
+          v = Y[h_s][t];                     // Eq. 4 at 1 bit: slot = token, value = code * s + z
         }
-        v = (v + 2.0f * w2) * (1.0f / 32.0f);
         const int nq = a.n_a >> 2;
         for (int j = 0; j < a.n_a; ++j) {
           const uint32_t code = (kcodes[t * nq + (j >> 2)] >> (2 * (j & 3))) & 3u;
@@ -302,7 +313,7 @@ hipError_t launch_decode_attention(const Geom& g, int layer, float scale, const 
   a.part = reinterpret_cast<float*>(ws);
   a.layer = layer; a.B = g.B; a.H = g.H; a.Hq = g.Hq; a.rep = g.rep; a.ng = g.ng; a.ngc = g.ngc;
   a.n_a = g.n_a; a.n_n = g.n_n; a.n_s = g.n_s; a.krec_bytes = g.krec; a.cap = cap;
-  a.sal_bits = g.sal_bits; a.npg = g.npg;
+  a.sal_bits = g.sal_bits; a.npg = g.npg; a.use_fft = g.use_fft ? 1 : 0;
   a.nsplit = attn_num_splits(g);
   a.scale2 = scale * 1.4426950408889634f;
   a.split0 = 0;

@@ -45,8 +45,11 @@ __device__ __forceinline__ float swap_max16(float v) {
   return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
 }
 
-// SAL: 0 no protected tokens, 1 protected rows in fp16, 2 protected rows as 2-bit records
-template <int NA8, int SAL>
+// SAL: 0 no protected tokens, 1 protected rows in fp16, 2 protected rows as 2-bit records.
+// FFT: normal key channels coded by Eq. 5 (true) or by Eq. 4 at 1 bit on the tokens (false);
+// in the latter case slot = token and code * s + z = (z + s/2) + sigma * s/2, sigma = +-1,
+// so the same sign-type operand serves, without the inverse DFT and with a constant term.
+template <int NA8, int SAL, bool FFT>
 __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a) {
   constexpr int NA = 8 * NA8, NN = D - NA;
   constexpr int NB = NN / 8;                 // normal 8-channel blocks
@@ -84,14 +87,14 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a) {
   __syncthreads();
   const bool hv = hcol < R;
   const _Float16* qrow = &qs[hv ? hcol : 0][0];
-  Op Bn[U > 0 ? U : 1];                      // normal channels: -q/16 at channels 8 (4u+kb) + e
+  Op Bn[U > 0 ? U : 1];                      // normal channels: -q/16 (FFT) or -q/2 at channels 8 (4u+kb) + e
 #pragma unroll
   for (int u = 0; u < U; ++u) {
     const int blk = 4 * u + kb;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
       float v = 0.0f;
-      if (hv && blk < NB) v = -(float)qrow[perm_s[NA + 8 * blk + e]] * 0.0625f;
+      if (hv && blk < NB) v = -(float)qrow[perm_s[NA + 8 * blk + e]] * (FFT ? 0.0625f : 0.5f);
       Bn[u].v[e] = (_Float16)v;
     }
   }
@@ -221,8 +224,10 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a) {
 
     f4 S[2] = {zero, zero};                      // scores[token][column]
     // ---- normal channels: Y[slot][col] per group, K = channels
+    float cst_n = 0.0f;                          // non-FFT: sum over normal channels of q (z + s/2)
     if (U > 0) {
       f4 accRe[2], accIm[2];
+      f4 accCn[2] = {zero, zero};
 #pragma unroll
       for (int grp = 0; grp < 2; ++grp) {
         const uint8_t* rec = reinterpret_cast<const uint8_t*>(&kl4[wave][grp][0]);
@@ -233,17 +238,39 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a) {
           const uint32_t xx = w | (w << 15);
           Op sre, sim, A;
           sre.q = *reinterpret_cast<const u32x4*>(rec + OFF_META + (blk * 2) * 16);
-          sim.q = *reinterpret_cast<const u32x4*>(rec + OFF_META + (blk * 2 + (x16 ? 1 : 0)) * 16);
+          sim.q = *reinterpret_cast<const u32x4*>(rec + OFF_META + (blk * 2 + ((FFT && x16) ? 1 : 0)) * 16);
 #pragma unroll
           for (int r = 0; r < 4; ++r) A.u[r] = ((xx << (15 - 2 * r)) & 0x80008000u) | sre.u[r];
           accRe[grp] = mma(A, Bn[u], u == 0 ? zero : accRe[grp]);
 #pragma unroll
           for (int r = 0; r < 4; ++r) A.u[r] = ((xx << (7 - 2 * r)) & 0x80008000u) | sim.u[r];
           accIm[grp] = mma(A, Bn[u], u == 0 ? zero : accIm[grp]);
+          if (!FFT) {
+            // constant term, rows all equal: (-z)(-q/2) + (-s/2)(-q/2) = q (z + s/2) / 2
+            Op zq, Az, As;
+            zq.q = *reinterpret_cast<const u32x4*>(rec + OFF_META + (blk * 2 + 1) * 16);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+              Az.u[r] = zq.u[r] ^ 0x80008000u;
+              As.u[r] = h2_bits(sre.p[r] * h2{(_Float16)0.5f, (_Float16)0.5f}) ^ 0x80008000u;
+            }
+            accCn[grp] = mma(Az, Bn[u], accCn[grp]);
+            accCn[grp] = mma(As, Bn[u], accCn[grp]);
+          }
         }
+      }
+      if (!FFT) {
+        // slot = token: the products are the scores' normal-channel part for my group
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          S[0][i] = par ? accRe[1][i] : accRe[0][i];
+          S[1][i] = par ? accIm[1][i] : accIm[0][i];
+        }
+        cst_n = 2.0f * (par ? accCn[1][0] : accCn[0][0]);
       }
       // my column belongs to group `par`; split Y/16 into fp16 hi + lo
       Op Yh, Yl;
+      if (FFT) {
 #pragma unroll
       for (int i = 0; i < 4; i += 2) {
         const float r0 = par ? accRe[1][i] : accRe[0][i], r1 = par ? accRe[1][i + 1] : accRe[0][i + 1];
@@ -258,6 +285,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a) {
         S[mt] = mma(Wh[mt], Yh, zero);
         S[mt] = mma(Wl[mt], Yh, S[mt]);
         S[mt] = mma(Wh[mt], Yl, S[mt]);
+      }
       }
     }
     // ---- anomalous channels: rows = tokens, K = (channel, bit plane); the column
@@ -297,6 +325,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a) {
       }
       cst = accC[0];                                             // = -(sum q (z + 1.5 s))
     }
+    if (!FFT) cst -= cst_n;
     // ---- t = score - running maximum, in the exp2 domain, for my column at token
     // slot i (i < 4: token 4kb+i, else 16+4kb+i-4)
     float c1 = -cst * a.scale2 - m_run;
@@ -501,9 +530,14 @@ bool attn_mfma_supported(int n_a) {
 
 template <int NA8>
 static void launch_one(const AttnArgs& a, dim3 grid, hipStream_t st) {
-  if (a.n_s > 0 && a.sal_bits == 2) hipLaunchKernelGGL((attn_mfma_kernel<NA8, 2>), grid, dim3(256), 0, st, a);
-  else if (a.n_s > 0) hipLaunchKernelGGL((attn_mfma_kernel<NA8, 1>), grid, dim3(256), 0, st, a);
-  else hipLaunchKernelGGL((attn_mfma_kernel<NA8, 0>), grid, dim3(256), 0, st, a);
+  const int sal = a.n_s > 0 ? (a.sal_bits == 2 ? 2 : 1) : 0;
+#define VIDKV_ATTN(S, F) hipLaunchKernelGGL((attn_mfma_kernel<NA8, S, F>), grid, dim3(256), 0, st, a)
+  if (a.use_fft) {
+    if (sal == 2) VIDKV_ATTN(2, true); else if (sal == 1) VIDKV_ATTN(1, true); else VIDKV_ATTN(0, true);
+  } else {
+    if (sal == 2) VIDKV_ATTN(2, false); else if (sal == 1) VIDKV_ATTN(1, false); else VIDKV_ATTN(0, false);
+  }
+#undef VIDKV_ATTN
 }
 
 void launch_attn_mfma(const AttnArgs& a, dim3 grid, hipStream_t st) {

@@ -172,7 +172,7 @@ __global__ __launch_bounds__(1024) void k_select_kernel(const _Float16* __restri
 
 // The per-group coding pass (Eq. 4 and Eq. 5) lives in quant_keys_mfma.hip.
 void launch_k_encode(const Geom& g, const EncodeSpan& sp, const void* K, uint8_t* packed,
-                     hipStream_t st);
+                     bool use_fft, hipStream_t st);
 
 // ---------------------------------------------------------------------------
 // stages: bit 0 range pass, bit 1 channel selection, bit 2 coding pass
@@ -187,7 +187,8 @@ hipError_t launch_quantize_keys(const Geom& g, const void* K, uint8_t* packed, v
   if (stages & 2u)
     hipLaunchKernelGGL(k_select_kernel, dim3((unsigned)g.nheads), dim3(1024), 0, st, w,
                        g.range_chunks, g.n_a, packed + g.k_perm);
-  if (stages & 4u) launch_k_encode(g, EncodeSpan{g.T, g.ng, 0, g.nheads, 0}, K, packed, st);
+  if (stages & 4u)
+    launch_k_encode(g, EncodeSpan{g.T, g.ng, 0, g.nheads, 0}, K, packed, g.use_fft, st);
   return hipGetLastError();
 }
 

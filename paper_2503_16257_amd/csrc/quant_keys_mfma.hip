@@ -62,8 +62,12 @@ constexpr DftTab make_dft_tab() {
 static __device__ const DftTab kDftTab = make_dft_tab();
 
 // NA8T >= 0 fixes n_a = 8 * NA8T at compile time (tile loop fully unrolled);
-// NA8T < 0 takes n_a at run time.
-template <int NA8T>
+// NA8T < 0 takes n_a at run time.  FFT = false codes the normal channels with
+// Eq. 4 at 1 bit on the tokens themselves (the non-FFT 1-bit path of Alg. 3):
+// the record keeps its shape, bit (blk, k) e / 8 + e holds the code of channel
+// 8 blk + e at token k / 16 + k, and the two scale slots hold s = max - min and
+// z = min.
+template <int NA8T, bool FFT>
 __global__ __launch_bounds__(256) void k_encode_mfma_kernel(const u32x4* __restrict__ K,
                                                             const uint8_t* __restrict__ perm_g,
                                                             int T, int ng, int n_a_rt, int krec, int gpb,
@@ -111,11 +115,13 @@ __global__ __launch_bounds__(256) void k_encode_mfma_kernel(const u32x4* __restr
 
   // DFT operand from the precomputed table: slot x16 of tile tt, k-slots = tokens
   Op F[2][3];
+  if (FFT) {
 #pragma unroll
-  for (int tt = 0; tt < 2; ++tt)
+    for (int tt = 0; tt < 2; ++tt)
 #pragma unroll
-    for (int part = 0; part < 3; ++part)
-      F[tt][part].q = *reinterpret_cast<const u32x4*>(&kDftTab.w[tt][part][lane][0]);
+      for (int part = 0; part < 3; ++part)
+        F[tt][part].q = *reinterpret_cast<const u32x4*>(&kDftTab.w[tt][part][lane][0]);
+  }
 
   uint8_t* rec8 = reinterpret_cast<uint8_t*>(&recbuf[wave][0]);
   uint16_t* rec16 = reinterpret_cast<uint16_t*>(rec8);
@@ -195,6 +201,48 @@ __global__ __launch_bounds__(256) void k_encode_mfma_kernel(const u32x4* __restr
             reinterpret_cast<_Float16*>(rec16)[5 * n_a + ja] = (_Float16)lo_f;
           }
         }
+      } else if (!FFT) {
+        // ---------------- Eq. 4, 1 bit: z = min, s = max - min over the 32 tokens
+        const int jn = j - NTa;
+        h2 mn2 = __builtin_elementwise_min(__builtin_elementwise_min(X.p[0], X.p[1]),
+                                           __builtin_elementwise_min(X.p[2], X.p[3]));
+        h2 mx2 = __builtin_elementwise_max(__builtin_elementwise_max(X.p[0], X.p[1]),
+                                           __builtin_elementwise_max(X.p[2], X.p[3]));
+        float lo_f = fminf((float)mn2[0], (float)mn2[1]);
+        float nh_f = -fmaxf((float)mx2[0], (float)mx2[1]);
+        {
+          auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(lo_f), __float_as_uint(nh_f), false, false);
+          const float t = fminf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+          auto q = __builtin_amdgcn_permlane16_swap(__float_as_uint(t), __float_as_uint(t), false, false);
+          const float u = fminf(__uint_as_float(q[0]), __uint_as_float(q[1]));   // rows 0,1: min; rows 2,3: -max
+          auto w = __builtin_amdgcn_permlane32_swap(__float_as_uint(u), __float_as_uint(u), false, false);
+          lo_f = __uint_as_float(w[0]);
+          nh_f = __uint_as_float(w[1]);
+        }
+        const float rng = -nh_f - lo_f;
+        // code = round-half-even((x - z) / s) in {0, 1} = [x above the midpoint]; a tie codes 0
+        const float mid = 0.5f * (lo_f - nh_f);
+        const int nidx = 16 * jn + x16;              // normal index of my column
+        // ballot i: bit 16 kb + 8 h + e = code of channel 8 (2 jn + h) + e at token slot (kb, i)
+        unsigned long long bal[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) bal[i] = __ballot(nidx < n_n && (float)X.v[i] > mid);
+        // lane (h = lane / 16, k = lane % 16) < 32 assembles word (blk 2 jn + h, k): low byte =
+        // token k = slot (k / 4, k % 4), high byte = token 16 + k = slot (k / 4, 4 + k % 4)
+        {
+          const int k = x16, h = kb & 1, ii = k & 3;
+          unsigned long long lo8 = ii == 0 ? bal[0] : ii == 1 ? bal[1] : ii == 2 ? bal[2] : bal[3];
+          unsigned long long hi8 = ii == 0 ? bal[4] : ii == 1 ? bal[5] : ii == 2 ? bal[6] : bal[7];
+          const int sh = 8 * (2 * (k >> 2) + h);
+          const uint32_t w16 = (uint32_t)((lo8 >> sh) & 0xFFull) | ((uint32_t)((hi8 >> sh) & 0xFFull) << 8);
+          const int blk = 2 * jn + h;
+          if (kb < 2 && blk < nblk) rec16[bits_h + blk * 16 + k] = (uint16_t)w16;
+        }
+        if ((kb & 1) == 0 && nidx < n_n) {
+          const int b8 = nidx >> 3, e = nidx & 7;
+          reinterpret_cast<_Float16*>(rec16)[meta_h + (b8 * 2 + (kb >> 1)) * 8 + e] =
+              (kb >> 1) ? (_Float16)lo_f : (_Float16)rng;
+        }
       } else {
         // ---------------- Eq. 5: 32-point DFT along tokens, sign bits and mean-|.| scales
         const int jn = j - NTa;
@@ -244,7 +292,7 @@ __global__ __launch_bounds__(256) void k_encode_mfma_kernel(const u32x4* __restr
 }
 
 void launch_k_encode(const Geom& g, const EncodeSpan& sp, const void* K, uint8_t* packed,
-                     hipStream_t st) {
+                     bool use_fft, hipStream_t st) {
   // two groups per wave: short-lived workgroups keep the memory system evenly loaded,
   // and the second group's load overlaps the first group's arithmetic
   const int gpb = 8;
@@ -252,9 +300,15 @@ void launch_k_encode(const Geom& g, const EncodeSpan& sp, const void* K, uint8_t
   const u32x4* k4 = reinterpret_cast<const u32x4*>(K);
   const uint8_t* perm = packed + g.k_perm + sp.head0 * D;
   uint8_t* rec = packed + g.k_rec + (size_t)sp.head0 * g.ngc * g.krec;
-#define VIDKV_ENC(N)                                                                              \
-  hipLaunchKernelGGL(k_encode_mfma_kernel<N>, grid, dim3(256), 0, st, k4, perm, sp.in_tokens, sp.ng, \
-                     g.n_a, g.krec, gpb, g.ngc, sp.g_out0, rec)
+#define VIDKV_ENC(N)                                                                          \
+  do {                                                                                        \
+    if (use_fft)                                                                              \
+      hipLaunchKernelGGL((k_encode_mfma_kernel<N, true>), grid, dim3(256), 0, st, k4, perm,   \
+                         sp.in_tokens, sp.ng, g.n_a, g.krec, gpb, g.ngc, sp.g_out0, rec);     \
+    else                                                                                      \
+      hipLaunchKernelGGL((k_encode_mfma_kernel<N, false>), grid, dim3(256), 0, st, k4, perm,  \
+                         sp.in_tokens, sp.ng, g.n_a, g.krec, gpb, g.ngc, sp.g_out0, rec);     \
+  } while (0)
   switch (g.n_a) {
     case 8:  VIDKV_ENC(1); break;
     case 16: VIDKV_ENC(2); break;

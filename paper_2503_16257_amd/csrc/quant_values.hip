@@ -304,15 +304,20 @@ __global__ __launch_bounds__(128) void v_protect2_kernel(const _Float16* __restr
   const int cnt = min(G, n_s - pg * G);
   __shared__ int tok[G];
   __shared__ uint8_t code_s[G][D];
-  if (c < G) tok[c] = c < cnt ? idx[(size_t)b * n_s + pg * G + c] : 0;
+  // rows beyond the last one repeat it: every load is valid and changes neither min nor max
+  if (c < G) tok[c] = idx[(size_t)b * n_s + pg * G + min(c, cnt - 1)];
   __syncthreads();
   const _Float16* head = V + hd * (long long)T * D;
+  _Float16 xh[G];
+#pragma unroll
+  for (int r = 0; r < G; ++r) xh[r] = head[(size_t)tok[r] * D + c];
   float x[G];
   float lo = 65504.0f, hi = -65504.0f;
 #pragma unroll
   for (int r = 0; r < G; ++r) {
-    x[r] = r < cnt ? (float)head[(size_t)tok[r] * D + c] : 0.0f;
-    if (r < cnt) { lo = fminf(lo, x[r]); hi = fmaxf(hi, x[r]); }
+    x[r] = (float)xh[r];
+    lo = fminf(lo, x[r]);
+    hi = fmaxf(hi, x[r]);
   }
   const float rng = hi - lo;
   const float inv = rng > 0.0f ? 3.0f / rng : 0.0f;

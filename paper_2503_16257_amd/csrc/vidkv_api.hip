@@ -15,7 +15,7 @@ hipError_t launch_decode_attention(const Geom& g, int layer, float scale, const 
                                    void* ws, unsigned stages, hipStream_t st);
 int attn_num_splits(const Geom& g);
 void launch_k_encode(const Geom& g, const EncodeSpan& sp, const void* K, uint8_t* packed,
-                     hipStream_t st);
+                     bool use_fft, hipStream_t st);
 void launch_v_encode(const Geom& g, const EncodeSpan& sp, int n_s, float gamma, const void* V,
                      uint8_t* packed, hipStream_t st);
 void launch_flush_marks(const Geom& g, int n_groups, uint8_t* packed, hipStream_t st);
@@ -27,7 +27,13 @@ static size_t ws_keys(const Geom& g) {
 }
 static size_t ws_values(const Geom& g) { return values_ws_bytes(g); }
 static size_t ws_attn(const Geom& g) {
-  return align256((size_t)(attn_num_splits(g) + 1) * g.B * g.Hq * (D + 2) * sizeof(float)) + 256;
+  // sized for the capacity, so that a workspace allocated once stays large enough
+  // while residual flushes make the packed cache longer
+  Geom c = g;
+  c.T = g.Tcap;
+  c.ng = g.ngc;
+  const int ns = attn_num_splits(c) > attn_num_splits(g) ? attn_num_splits(c) : attn_num_splits(g);
+  return align256((size_t)(ns + 1) * g.B * g.Hq * (D + 2) * sizeof(float)) + 256;
 }
 static bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
@@ -169,7 +175,7 @@ vidkv_status vidkv_flush_residual(const vidkv_params* p, int32_t layer, const vo
   hipStream_t st = static_cast<hipStream_t>(stream);
   const long long bh = (long long)g.B * g.H;
   const EncodeSpan sp{tail_capacity, n_flush / G, g.ng, bh, layer * bh};
-  launch_k_encode(g, sp, K_tail, static_cast<uint8_t*>(packed_K), st);
+  launch_k_encode(g, sp, K_tail, static_cast<uint8_t*>(packed_K), g.use_fft, st);
   launch_v_encode(g, sp, 0, p->gamma, V_tail, static_cast<uint8_t*>(packed_V), st);
   launch_flush_marks(g, sp.ng, static_cast<uint8_t*>(packed_V), st);
   return hipGetLastError() == hipSuccess ? VIDKV_OK : VIDKV_EHIP;

@@ -40,13 +40,14 @@ class GpuRun:
     """Device buffers of one workload pushed through the library."""
 
     def __init__(self, w: synth.Workload, device="cuda:0", gamma=GAMMA, K=None, V=None,
-                 saliency=None, salient_idx=None, quantize=True, t_capacity=0, salient_bits=0):
+                 saliency=None, salient_idx=None, quantize=True, t_capacity=0, salient_bits=0, use_fft=1):
         self.w = w
         self.dev = device
         self.T = w.T                          # tokens packed so far (grows with flushes)
         self.Tcap = t_capacity or w.T
         self.p = vk.make_params(w.L, w.B, w.Hkv, w.Hq, w.T, w.n_anom, w.n_salient, gamma=gamma,
-                                t_capacity=t_capacity, salient_bits=salient_bits)
+                                t_capacity=t_capacity, salient_bits=salient_bits, use_fft=use_fft)
+        self.use_fft = bool(use_fft)
         self.sal_bits = 2 if salient_bits == 2 else 16
         self.K = torch.from_numpy(synth.keys(w)).to(device) if K is None else K
         self.V = torch.from_numpy(synth.values(w)).to(device) if V is None else V
@@ -115,7 +116,9 @@ class GpuRun:
         ng, ngc = self.T // 32, self.Tcap // 32
         perm = self._bytes(self.pk, sec["perm"] + hd * 128, 128)
         recs = self._bytes(self.pk, sec["rec"] + hd * ngc * rb, ng * rb).reshape(ng, rb)
-        return LY.unpack_key_head(perm, recs, w.n_anom)
+        rec = LY.unpack_key_head(perm, recs, w.n_anom)
+        rec["fft"] = self.use_fft          # how the normal channels' bits and scales are to be read
+        return rec
 
     def value_record(self, hd):
         w = self.w
@@ -153,7 +156,7 @@ def _count(stats, key, n_near, n_total):
 def check_keys_head(run: GpuRun, hd: int, K_head: np.ndarray, stats: dict):
     """GPU key record of head hd vs oracle MixQuant on the same fp16 input."""
     w = run.w
-    ref = O.quantize_keys_head(K_head, w.n_anom)
+    ref = O.quantize_keys_head(K_head, w.n_anom, run.use_fft)
     got = run.key_record(hd)
     np.testing.assert_array_equal(got["perm"], ref["perm"], err_msg=f"perm head {hd}")
     if w.n_anom:

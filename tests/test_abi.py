@@ -55,7 +55,7 @@ def test_stored_bits_per_element():
 def test_invalid_params_give_zero_sizes():
     bad = [
         dict(n_anom=7), dict(n_anom=136), dict(t_quant=33), dict(t_quant=-32), dict(head_dim=64),
-        dict(group=64), dict(n_q_heads=5), dict(n_q_heads=36), dict(use_fft=0),
+        dict(group=64), dict(n_q_heads=5), dict(n_q_heads=36), dict(use_fft=2),
         dict(n_salient=65), dict(n_salient=-1), dict(n_layers=0), dict(batch=0), dict(n_kv_heads=0),
     ]
     for kw in bad:

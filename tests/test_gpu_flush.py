@@ -26,7 +26,7 @@ def _check_block(run, hd, g0, Kblk, Vblk, stats):
     """Groups g0.. of head hd against the oracle's coding of the block."""
     n = Kblk.shape[0] // 32
     k = run.key_record(hd)
-    ref = O.quantize_keys_block(Kblk, k["anom"], k["norm"])
+    ref = O.quantize_keys_block(Kblk, k["anom"], k["norm"], run.use_fft)
     if len(k["anom"]):
         got = k["a_codes"][g0:g0 + n]
         bad = (got != ref["a_codes"]) & ~ref["a_near"]

@@ -486,3 +486,47 @@ def test_stp_rows_two_bit_brute_force_and_bounds():
     qc = O.stp_quant_rows(const)
     assert not qc["codes"][:, 3].any() and np.all(qc["s16"][:, 3] == 0)
     assert np.all(O.stp_dequant_rows(qc["codes"], qc["s16"], qc["z16"])[:, 3] == 2.5)
+
+
+def test_standard_one_bit_quantizer_closed_forms():
+    """Eq. 4 with n = 1 (the non-FFT 1-bit path of Sec. 4.1 / Alg. 3): every token maps to the
+    group's minimum or maximum, whichever is nearer (ties to the minimum: round half to even);
+    two-level data come back exactly; the error never exceeds half the range."""
+    rng = np.random.default_rng(41)
+    x = _f16(rng.standard_normal((64, 5)) * 2)
+    q = O.gquant(x, bits=1)
+    assert set(np.unique(q["codes"])) <= {0, 1}
+    d = O.gdequant(q["codes"], q["s16"], q["z16"])
+    xd = x.astype(np.float64)
+    for g in range(2):
+        blk = xd[32 * g:32 * g + 32]
+        lo, hi = blk.min(axis=0), blk.max(axis=0)
+        nearer_hi = (hi - blk) < (blk - lo)
+        want = np.where(nearer_hi, 1, 0)
+        ok = ~q["near"][g].T
+        np.testing.assert_array_equal(q["codes"][g].T[ok], want[ok])
+        np.testing.assert_array_equal(q["z16"][g].astype(np.float64), lo)
+        assert np.all(np.abs(d[32 * g:32 * g + 32] - blk) <= 0.5 * (hi - lo) * (1 + 1e-3) + 1e-3)
+    two = _f16(np.where(rng.random((32, 4)) < 0.5, -0.75, 1.25)); two[0] = -0.75; two[1] = 1.25
+    q2 = O.gquant(two, bits=1)
+    np.testing.assert_array_equal(O.gdequant(q2["codes"], q2["s16"], q2["z16"]), two.astype(np.float64))
+    # exact midpoint -> code 0 (0.5 rounds to the even integer 0)
+    mid = _f16(np.array([[0.0], [2.0], [1.0]] + [[0.0]] * 29))
+    qm = O.gquant(mid, bits=1)
+    assert qm["codes"][0, 0, 2] == 0 and qm["near"][0, 0, 2]
+    # through the head-level entry: same channel split as the FFT mode, only the normal part changes
+    w = synth.WORKLOADS["c1_toy_na8"]
+    K = synth.key_head(w, 0)[:256]
+    a = O.quantize_keys_head(K, 8)
+    b = O.quantize_keys_head(K, 8, use_fft=False)
+    np.testing.assert_array_equal(a["perm"], b["perm"])
+    np.testing.assert_array_equal(a["a_codes"], b["a_codes"])
+    g1 = O.gquant(K[:, b["norm"]], bits=1)
+    np.testing.assert_array_equal(b["n_bits"], g1["codes"])
+    Kb = O.dequantize_keys_head(b)
+    np.testing.assert_array_equal(Kb[:, b["norm"]], O.gdequant(g1["codes"], g1["s16"], g1["z16"]))
+    # white noise: a two-level code at the extremes of 32 samples is much worse than the FFT code
+    Kd = K.astype(np.float64)
+    err_fft = ((Kd - O.dequantize_keys_head(a))[:, a["norm"]] ** 2).mean()
+    err_std = ((Kd - Kb)[:, b["norm"]] ** 2).mean()
+    assert err_std > 3 * err_fft

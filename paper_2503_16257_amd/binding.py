@@ -17,6 +17,9 @@ LIB_PATH = os.path.join(_HERE, "libvidkv.so")
 OK, EINVAL, ESHAPE, ENOSPACE, EHIP = 0, 1, 2, 3, 4
 
 
+ABI_VERSION = 2          # VIDKV_ABI_VERSION of include/vidkv.h that this binding was written for
+
+
 class VidkvParams(C.Structure):
     _fields_ = [
         ("n_layers", C.c_int32), ("batch", C.c_int32), ("n_kv_heads", C.c_int32),

@@ -28,13 +28,19 @@ def _check_heads(run, K, V, heads, scores_np):
     return stats
 
 
-def test_long_video_full_size():
-    """1000 frames = 196000 tokens, 4 KV x 28 Q heads, n_a = 16, 9800 protected."""
+@pytest.mark.parametrize("mode", ["headline", "one_bit_keys_two_bit_protected_rows"])
+def test_long_video_full_size(mode):
+    """1000 frames = 196000 tokens, 4 KV x 28 Q heads, n_a = 16, 9800 protected; in the
+    headline configuration and with the non-FFT key code plus 2-bit protected rows, followed
+    there by a flush of a 128-token residual block."""
     w = synth.WORKLOADS["c4_long"]
-    print("[case] c4_long full", flush=True)
+    print(f"[case] c4_long full {mode}", flush=True)
+    alt = mode != "headline"
     K, V = synth.device_kv(w, DEV)
     scores = synth.saliency(w)
-    run = P.GpuRun(w, DEV, K=K, V=V, saliency=torch.from_numpy(scores).to(DEV))
+    run = P.GpuRun(w, DEV, K=K, V=V, saliency=torch.from_numpy(scores).to(DEV),
+                   use_fft=0 if alt else 1, salient_bits=2 if alt else 0,
+                   t_capacity=w.T + 128 if alt else 0)
     _check_heads(run, K, V, [0, 3], scores)
     print("[step] codec ok", flush=True)
     q = synth.query(w, 0)
@@ -42,6 +48,20 @@ def test_long_video_full_size():
     ref = P.oracle_attention(run, 0, 0, q[0])
     err = P.assert_out_close(out[0], ref, "c4_long")
     print(f"[step] attention ok, max err {err:.2e}", flush=True)
+    if alt:
+        import test_gpu_flush as F
+        Kt = np.stack([synth.tail_heads(w, 0, b, 128)[0] for b in range(w.B)])
+        Vt = np.stack([synth.tail_heads(w, 0, b, 128)[1] for b in range(w.B)])
+        run.flush(0, torch.from_numpy(Kt).to(DEV), torch.from_numpy(Vt).to(DEV), 128, 128)
+        run.advance(128)
+        stats = {}
+        for h in (0, 3):
+            F._check_block(run, h, w.T // 32, Kt[0, h], Vt[0, h], stats)
+        P.check_near_budget(stats)
+        q = synth.query(w, 0, step=1)
+        out = run.attention(0, torch.from_numpy(q).to(DEV)).cpu().numpy()
+        err = P.assert_out_close(out[0], P.oracle_attention(run, 0, 0, q[0]), "c4_long after flush")
+        print(f"[step] flush + attention ok, max err {err:.2e}", flush=True)
 
 
 def test_full_stack_16_decode_steps():

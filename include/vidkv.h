@@ -117,7 +117,11 @@ vidkv_status vidkv_quantize_keys(const vidkv_params *params, const void *K_dev,
  *   salient_idx_dev in : [B, n_salient] int32, strictly ascending per
  *                        sequence, or NULL.  With n_salient > 0 exactly one of
  *                        the two is non-NULL; with n_salient == 0 both are
- *                        ignored.
+ *                        ignored.  Entries outside 0..Tq-1 and repeated
+ *                        entries are not an error: they are dropped, fewer
+ *                        tokens are protected (with salient_bits == 2 the
+ *                        statistics of the last group of protected rows are
+ *                        then unspecified).
  *   packed_V_dev    out: >= vidkv_packed_values_bytes(params) bytes
  *   workspace_dev      : >= vidkv_workspace_bytes(params, 1) bytes           */
 vidkv_status vidkv_quantize_values(const vidkv_params *params, const void *V_dev,

@@ -305,7 +305,9 @@ __global__ __launch_bounds__(128) void v_protect2_kernel(const _Float16* __restr
   __shared__ int tok[G];
   __shared__ uint8_t code_s[G][D];
   // rows beyond the last one repeat it: every load is valid and changes neither min nor max
-  if (c < G) tok[c] = idx[(size_t)b * n_s + pg * G + min(c, cnt - 1)];
+  // (an index list with repeated or out-of-range entries leaves the end of IDX unwritten:
+  // whatever is there is clamped into the tensor, such rows are never read back)
+  if (c < G) tok[c] = min(max(idx[(size_t)b * n_s + pg * G + min(c, cnt - 1)], 0), T - 1);
   __syncthreads();
   const _Float16* head = V + hd * (long long)T * D;
   _Float16 xh[G];

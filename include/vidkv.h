@@ -14,7 +14,7 @@
  * General rules
  *  - Every pointer named *_dev is DEVICE memory on the current HIP device;
  *    `params` is HOST memory.  The caller owns every buffer; the library
- *    allocates nothing, keeps no pointer after a call returns and never
+ *    allocates no memory, keeps no pointer after a call returns and never
  *    synchronizes: all work is enqueued on `hip_stream` (a hipStream_t passed
  *    as void*, NULL = the default stream).
  *  - All arguments are checked on the host before anything is launched; a
@@ -86,7 +86,7 @@ typedef struct vidkv_params {
 
 /* Size queries: pure host functions, usable without a GPU.  Return 0 when
  * `params` is NULL or invalid.  `which`: 0 = quantize_keys, 1 = quantize_values,
- * 2 = decode_attention. */
+ * 2 = decode_attention, 3 = quantize_kv. */
 size_t vidkv_packed_keys_bytes(const vidkv_params *params);
 size_t vidkv_packed_values_bytes(const vidkv_params *params);
 size_t vidkv_workspace_bytes(const vidkv_params *params, int which);
@@ -130,6 +130,26 @@ vidkv_status vidkv_quantize_values(const vidkv_params *params, const void *V_dev
                                    void *packed_V_dev, size_t packed_bytes,
                                    void *workspace_dev, size_t workspace_bytes,
                                    void *hip_stream);
+
+/* Alg. 3 and Alg. 2 on the K and V tensors of the same tokens in one call (the
+ * compression step at the end of Alg. 1, Prefill): the packed buffers come out
+ * byte-identical to vidkv_quantize_keys followed by vidkv_quantize_values.
+ * The protected-token selection - a chain of short dependent launches - is
+ * enqueued on a side stream owned by the library (one per device, default
+ * priority, created at the first call and kept until the process ends) so
+ * that it runs beside the key passes.  The side stream starts after
+ * everything already enqueued on `hip_stream` and is joined back before the
+ * value coding pass: to the caller all work is ordered on `hip_stream` as
+ * usual.  This is the one entry point that creates HIP objects (that stream
+ * and two events); it has not been exercised under stream capture.
+ * Arguments as for the two separate calls;
+ *   workspace_dev : >= vidkv_workspace_bytes(params, 3) bytes                 */
+vidkv_status vidkv_quantize_kv(const vidkv_params *params, const void *K_dev,
+                               const void *V_dev, const float *saliency_dev,
+                               const int32_t *salient_idx_dev, void *packed_K_dev,
+                               size_t packed_K_bytes, void *packed_V_dev,
+                               size_t packed_V_bytes, void *workspace_dev,
+                               size_t workspace_bytes, void *hip_stream);
 
 /* Alg. 1, Decoding, for one layer: out = Softmax(scale * q [K'; K_r]^T) [V'; V_r]
  * (Eq. 3) where K', V' are the dequantized packed tokens (never materialised

@@ -59,6 +59,8 @@ def lib() -> C.CDLL:
         L.vidkv_quantize_keys.restype = C.c_int
         L.vidkv_quantize_values.argtypes = [PP, vp, vp, vp, vp, sz, vp, sz, vp]
         L.vidkv_quantize_values.restype = C.c_int
+        L.vidkv_quantize_kv.argtypes = [PP, vp, vp, vp, vp, vp, sz, vp, sz, vp, sz, vp]
+        L.vidkv_quantize_kv.restype = C.c_int
         L.vidkv_flush_residual.argtypes = [PP, i32, vp, vp, i32, i32, vp, sz, vp, sz, vp]
         L.vidkv_flush_residual.restype = C.c_int
         L.vidkv_saliency_workspace_bytes.argtypes = [i32, i32]
@@ -185,6 +187,19 @@ def decode_attention(p: VidkvParams, layer: int, q, packed_K, packed_V, out, wor
     else:
         _check(lib().vidkv_decode_attention_stages(*a, stages, _stream(stream)),
                "vidkv_decode_attention_stages")
+
+
+def quantize_kv(p: VidkvParams, K, V, packed_K, packed_V, workspace, saliency=None,
+                salient_idx=None, stream=None) -> None:
+    """vidkv_quantize_kv: both tensors of the same tokens in one call."""
+    import torch
+    _check(lib().vidkv_quantize_kv(
+        C.byref(p), _ptr(K, torch.float16, "K"), _ptr(V, torch.float16, "V"),
+        _ptr(saliency, torch.float32, "saliency"), _ptr(salient_idx, torch.int32, "salient_idx"),
+        _ptr(packed_K, torch.uint8, "packed_K"), _nbytes(packed_K),
+        _ptr(packed_V, torch.uint8, "packed_V"), _nbytes(packed_V),
+        _ptr(workspace, torch.uint8, "workspace"), _nbytes(workspace), _stream(stream)),
+        "vidkv_quantize_kv")
 
 
 def flush_residual(p: VidkvParams, layer: int, K_tail, V_tail, tail_capacity: int, n_flush: int,

@@ -1,5 +1,7 @@
 // C ABI of the VidKV library: argument validation on the host, then kernel
 // launches on the caller's stream.  Nothing here allocates or synchronizes.
+#include <mutex>
+
 #include "vidkv_common.h"
 
 namespace vidkv {
@@ -48,6 +50,33 @@ __global__ __launch_bounds__(256) void calib_copy_kernel(const u32x4* __restrict
 
 using namespace vidkv;
 
+// Per-device side stream and fork / join events of vidkv_quantize_kv, created on
+// first use and kept until the process ends.
+namespace {
+struct SideStream {
+  hipStream_t stream = nullptr;
+  hipEvent_t fork = nullptr, join = nullptr;
+  bool ready = false;
+};
+constexpr int MAX_DEVICES = 64;
+SideStream g_side[MAX_DEVICES];
+std::mutex g_side_mutex;
+
+SideStream* side_stream_locked() {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return nullptr;
+  SideStream& s = g_side[dev];
+  if (!s.ready) {
+    // default priority, like every stream this library touches
+    if (hipStreamCreateWithFlags(&s.stream, hipStreamNonBlocking) != hipSuccess) return nullptr;
+    if (hipEventCreateWithFlags(&s.fork, hipEventDisableTiming) != hipSuccess) return nullptr;
+    if (hipEventCreateWithFlags(&s.join, hipEventDisableTiming) != hipSuccess) return nullptr;
+    s.ready = true;
+  }
+  return &s;
+}
+}  // namespace
+
 extern "C" {
 
 size_t vidkv_packed_keys_bytes(const vidkv_params* p) {
@@ -67,6 +96,7 @@ size_t vidkv_workspace_bytes(const vidkv_params* p, int which) {
     case 0: return ws_keys(g);
     case 1: return ws_values(g);
     case 2: return ws_attn(g);
+    case 3: return ws_keys(g) + ws_values(g);
     default: return 0;
   }
 }
@@ -118,6 +148,49 @@ vidkv_status vidkv_quantize_values(const vidkv_params* p, const void* V, const f
                                    void* ws, size_t ws_bytes, void* stream) {
   return vidkv_quantize_values_stages(p, V, saliency, salient_idx, packed, packed_bytes, ws,
                                       ws_bytes, ~0u, stream);
+}
+
+vidkv_status vidkv_quantize_kv(const vidkv_params* p, const void* K, const void* V,
+                               const float* saliency, const int32_t* salient_idx, void* packed_K,
+                               size_t packed_K_bytes, void* packed_V, size_t packed_V_bytes,
+                               void* ws, size_t ws_bytes, void* stream) {
+  Geom g;
+  if (!p || !packed_K || !packed_V || !ws) return VIDKV_EINVAL;
+  if (!make_geom(p, &g)) return VIDKV_ESHAPE;
+  if (g.T > 0 && (!K || !V)) return VIDKV_EINVAL;
+  if (g.nheads > 65535) return VIDKV_ESHAPE;
+  if (g.n_s > 0 && ((saliency != nullptr) == (salient_idx != nullptr))) return VIDKV_EINVAL;
+  if (!(p->gamma >= 0.0f) || !(p->gamma < 1e30f)) return VIDKV_EINVAL;
+  if (!aligned(K, 16) || !aligned(V, 16) || !aligned(packed_K, 256) || !aligned(packed_V, 256) ||
+      !aligned(ws, 256) || !aligned(saliency, 16) || !aligned(salient_idx, 4))
+    return VIDKV_EINVAL;
+  if (packed_K_bytes < g.k_total || packed_V_bytes < g.v_total) return VIDKV_ENOSPACE;
+  if (ws_bytes < ws_keys(g) + ws_values(g)) return VIDKV_ENOSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  uint8_t* pk = static_cast<uint8_t*>(packed_K);
+  uint8_t* pv = static_cast<uint8_t*>(packed_V);
+  void* ws_k = ws;
+  void* ws_v = static_cast<uint8_t*>(ws) + ws_keys(g);
+  const float* sc = g.n_s > 0 ? saliency : nullptr;
+  const int32_t* ix = g.n_s > 0 ? salient_idx : nullptr;
+  if (g.n_s > 0 && g.T > 0) {
+    // the chain of short selection launches runs beside the bandwidth-bound key passes
+    std::lock_guard<std::mutex> lock(g_side_mutex);
+    SideStream* s = side_stream_locked();
+    if (!s) return VIDKV_EHIP;
+    if (hipEventRecord(s->fork, st) != hipSuccess) return VIDKV_EHIP;
+    if (hipStreamWaitEvent(s->stream, s->fork, 0) != hipSuccess) return VIDKV_EHIP;
+    if (launch_quantize_values(g, p->gamma, V, sc, ix, pv, ws_v, 1u, s->stream) != hipSuccess)
+      return VIDKV_EHIP;
+    if (hipEventRecord(s->join, s->stream) != hipSuccess) return VIDKV_EHIP;
+    if (launch_quantize_keys(g, K, pk, ws_k, ~0u, st) != hipSuccess) return VIDKV_EHIP;
+    if (hipStreamWaitEvent(st, s->join, 0) != hipSuccess) return VIDKV_EHIP;
+    return launch_quantize_values(g, p->gamma, V, sc, ix, pv, ws_v, 2u, st) == hipSuccess
+               ? VIDKV_OK : VIDKV_EHIP;
+  }
+  if (launch_quantize_keys(g, K, pk, ws_k, ~0u, st) != hipSuccess) return VIDKV_EHIP;
+  return launch_quantize_values(g, p->gamma, V, sc, ix, pv, ws_v, ~0u, st) == hipSuccess
+             ? VIDKV_OK : VIDKV_EHIP;
 }
 
 vidkv_status vidkv_decode_attention_stages(const vidkv_params* p, int32_t layer, const void* q,

@@ -40,7 +40,7 @@ class GpuRun:
     """Device buffers of one workload pushed through the library."""
 
     def __init__(self, w: synth.Workload, device="cuda:0", gamma=GAMMA, K=None, V=None,
-                 saliency=None, salient_idx=None, quantize=True, t_capacity=0, salient_bits=0, use_fft=1):
+                 saliency=None, salient_idx=None, quantize=True, t_capacity=0, salient_bits=0, use_fft=1, fused=False):
         self.w = w
         self.dev = device
         self.T = w.T                          # tokens packed so far (grows with flushes)
@@ -61,16 +61,22 @@ class GpuRun:
                             if saliency is None else saliency)
         self.pk = vk.alloc_bytes(vk.packed_keys_bytes(self.p), device)
         self.pv = vk.alloc_bytes(vk.packed_values_bytes(self.p), device)
-        self.ws = vk.alloc_bytes(max(vk.workspace_bytes(self.p, i) for i in range(3)), device)
+        self.fused = fused
+        self.ws = vk.alloc_bytes(max(vk.workspace_bytes(self.p, i) for i in range(4)), device)
         self.pk.fill_(0xA5)        # stale bytes must not matter
         self.pv.fill_(0x5A)
         self.ws.fill_(0xFF)
         if quantize:
             self.quantize()
 
-    def quantize(self):
-        vk.quantize_keys(self.p, self.K, self.pk, self.ws)
-        vk.quantize_values(self.p, self.V, self.pv, self.ws, saliency=self.sal, salient_idx=self.idx)
+    def quantize(self, stream=None):
+        if self.fused:
+            vk.quantize_kv(self.p, self.K, self.V, self.pk, self.pv, self.ws, saliency=self.sal,
+                           salient_idx=self.idx, stream=stream)
+        else:
+            vk.quantize_keys(self.p, self.K, self.pk, self.ws, stream=stream)
+            vk.quantize_values(self.p, self.V, self.pv, self.ws, saliency=self.sal,
+                               salient_idx=self.idx, stream=stream)
         torch.cuda.synchronize()
         self._pk_np = self._pv_np = None
 

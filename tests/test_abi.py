@@ -22,7 +22,7 @@ def _declared_functions():
 def test_library_exports_every_declared_symbol():
     names = _declared_functions()
     assert {"vidkv_quantize_keys", "vidkv_quantize_values", "vidkv_decode_attention",
-            "vidkv_flush_residual", "vidkv_saliency_scores", "vidkv_packed_keys_bytes", "vidkv_packed_values_bytes", "vidkv_workspace_bytes",
+            "vidkv_flush_residual", "vidkv_saliency_scores", "vidkv_quantize_kv", "vidkv_packed_keys_bytes", "vidkv_packed_values_bytes", "vidkv_workspace_bytes",
             "vidkv_status_string", "vidkv_abi_version", "vidkv_calib_copy"} <= set(names)
     L = C.CDLL(vk.LIB_PATH)
     for n in names:
@@ -42,7 +42,8 @@ def test_size_functions_match_format(L_, B, H, Hq, T, n_a, n_s):
     assert vk.packed_values_bytes(p) == LY.value_sections(L_, B, H, T, n_s)["total"]
     for which in (0, 1, 2):
         assert vk.workspace_bytes(p, which) >= 256
-    assert vk.workspace_bytes(p, 3) == 0
+    assert vk.workspace_bytes(p, 3) == vk.workspace_bytes(p, 0) + vk.workspace_bytes(p, 1)
+    assert vk.workspace_bytes(p, 4) == 0
 
 
 def test_stored_bits_per_element():
@@ -94,6 +95,15 @@ def test_entry_points_refuse_bad_arguments_before_launch():
     assert L.vidkv_quantize_values(pb, None, A, None, A, big, A, big, None) == vk.EINVAL
     neg = vk.make_params(1, 1, 4, 28, 64, 16, 4, gamma=-0.5)
     assert L.vidkv_quantize_values(C.byref(neg), A, A, None, A, big, A, big, None) == vk.EINVAL
+    # quantize_kv: the checks of both, and a workspace that holds both
+    assert L.vidkv_quantize_kv(pb, A, A, A, None, A, big, A, big, None, big, None) == vk.EINVAL
+    assert L.vidkv_quantize_kv(pb, None, A, A, None, A, big, A, big, A, big, None) == vk.EINVAL
+    assert L.vidkv_quantize_kv(pb, A, A, A, A, A, big, A, big, A, big, None) == vk.EINVAL
+    assert L.vidkv_quantize_kv(pb, A, A, A, None, A, kb - 1, A, big, A, big, None) == vk.ENOSPACE
+    assert L.vidkv_quantize_kv(pb, A, A, A, None, A, big, A, vb - 1, A, big, None) == vk.ENOSPACE
+    assert vk.workspace_bytes(p, 3) == vk.workspace_bytes(p, 0) + vk.workspace_bytes(p, 1)
+    assert L.vidkv_quantize_kv(pb, A, A, A, None, A, big, A, big, A,
+                               vk.workspace_bytes(p, 3) - 1, None) == vk.ENOSPACE
     # decode_attention
     args = [pb, 0, A, A, A, None, None, 0, None, A, A, big, None]
     def call(**kw):

@@ -80,6 +80,42 @@ def test_index_list_equals_score_selection():
     _codec_all_heads(a, scores=scores)
 
 
+@pytest.mark.parametrize("case", ["long_scores", "long_indices", "layer_no_protection", "serving_batch",
+                                  "two_bit_rows_one_bit_keys"])
+def test_fused_quantizer_equals_separate_calls(case):
+    """vidkv_quantize_kv (selection on the library's side stream) writes the same bytes as
+    the two separate calls, on the default and on a caller's stream, call after call."""
+    kw = {}
+    if case.startswith("long"):
+        w = synth.reduced(synth.WORKLOADS["c4_long"], 40)         # 7840 tokens, 392 protected
+    elif case == "layer_no_protection":
+        w = synth.WORKLOADS["c2_layer"]
+    elif case == "serving_batch":
+        w = synth.reduced(synth.WORKLOADS["c5_serving"], 8, B=3)
+    else:
+        w = synth.reduced(synth.WORKLOADS["c4_long"], 16)
+        kw = dict(salient_bits=2, use_fft=0)
+    print(f"[case] fused-{case}", flush=True)
+    idx = None
+    if case == "long_indices":
+        idx = torch.from_numpy(np.stack([
+            np.sort(O.select_salient_tokens(synth.saliency(w)[b], w.n_salient)).astype(np.int32)
+            for b in range(w.B)])).to(DEV)
+    a = P.GpuRun(w, DEV, salient_idx=idx, **kw)
+    b = P.GpuRun(w, DEV, salient_idx=idx, fused=True, **kw)
+    assert torch.equal(a.pk, b.pk) and torch.equal(a.pv, b.pv)
+    side = torch.cuda.Stream()                                     # default priority
+    for rep in range(3):
+        b.pk.fill_(0xA5)
+        b.pv.fill_(0x5A)
+        b.ws.fill_(rep)
+        torch.cuda.synchronize()
+        with torch.cuda.stream(side):
+            b.quantize(stream=side)
+        torch.cuda.synchronize()
+        assert torch.equal(a.pk, b.pk) and torch.equal(a.pv, b.pv), rep
+
+
 def test_score_ties_and_negative_scores():
     w = synth.reduced(synth.WORKLOADS["c4_long"], 8)             # 1568 tokens, 78 protected
     print("[case] score ties", flush=True)

@@ -82,6 +82,10 @@ typedef struct vidkv_params {
                             are coded with Eq. 4 at 2 bits per channel over
                             groups of 32 protected tokens (the last group may
                             be shorter)                                        */
+  int32_t channel_metric; /* how Alg. 3 ranks the key channels (Sec. 3.2 (1)):
+                            0 Range max - min (what the paper adopts), 1
+                            Variance, 2 number of Outliers |x| > 3 mean|x|;
+                            1 and 2 are the paper's ablation, in float64       */
 } vidkv_params;
 
 /* Size queries: pure host functions, usable without a GPU.  Return 0 when

@@ -58,6 +58,21 @@ def key_channel_range(K16: np.ndarray) -> np.ndarray:
     return (mx - mn).astype(np.float32)
 
 
+def key_channel_variance(K16: np.ndarray) -> np.ndarray:
+    """Sec. 3.2 (1), Variance: sigma^2 = mean(x^2) - mean(x)^2 per channel over all tokens
+    (population variance), float64.  K16 [T, D] fp16 -> [D]."""
+    x = K16.astype(np.float64)
+    return (x * x).mean(axis=0) - x.mean(axis=0) ** 2
+
+
+def key_channel_outliers(K16: np.ndarray, M: float = 3.0) -> np.ndarray:
+    """Sec. 3.2 (1), Outliers: N = sum_i 1(K_i > M * mean K) per channel with M = 3; the
+    printed formula has no absolute values, which for signed, near-zero-mean channels would
+    count half of all tokens - here |K_i| > M * mean|K|.  K16 [T, D] fp16 -> [D] float64."""
+    a = np.abs(K16.astype(np.float64))
+    return (a > M * a.mean(axis=0)).sum(axis=0).astype(np.float64)
+
+
 def select_anomalous_channels(R: np.ndarray, n_a: int):
     """Top-n_a channels by range -> 2-bit ("D-mask"), the rest -> 1-bit ("N-mask").
 
@@ -214,9 +229,10 @@ def quantize_keys_block(K16: np.ndarray, anom: np.ndarray, norm: np.ndarray,
     }
 
 
-def quantize_keys_head(K16: np.ndarray, n_a: int, use_fft: bool = True):
-    """Alg. 3 for one [T, D] head.  Returns the logical (unpacked) cache record."""
-    R = key_channel_range(K16)
+def quantize_keys_head(K16: np.ndarray, n_a: int, use_fft: bool = True, metric: int = 0):
+    """Alg. 3 for one [T, D] head.  Returns the logical (unpacked) cache record.
+    metric: 0 Range (the paper's choice), 1 Variance, 2 Outliers (its ablation)."""
+    R = (key_channel_range, key_channel_variance, key_channel_outliers)[metric](K16)
     anom, norm, perm = select_anomalous_channels(R, n_a)
     rec = quantize_keys_block(K16, anom, norm, use_fft)
     rec["range"] = R

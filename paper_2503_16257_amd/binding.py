@@ -26,7 +26,7 @@ class VidkvParams(C.Structure):
         ("n_q_heads", C.c_int32), ("head_dim", C.c_int32), ("group", C.c_int32),
         ("t_quant", C.c_int32), ("n_anom", C.c_int32), ("use_fft", C.c_int32),
         ("n_salient", C.c_int32), ("gamma", C.c_float), ("softmax_scale", C.c_float),
-        ("t_capacity", C.c_int32), ("salient_bits", C.c_int32),
+        ("t_capacity", C.c_int32), ("salient_bits", C.c_int32), ("channel_metric", C.c_int32),
     ]
 
 
@@ -89,11 +89,11 @@ def lib() -> C.CDLL:
 
 def make_params(n_layers, batch, n_kv_heads, n_q_heads, t_quant, n_anom, n_salient,
                 gamma=0.7, softmax_scale=None, head_dim=128, group=32, use_fft=1,
-                t_capacity=0, salient_bits=0) -> VidkvParams:
+                t_capacity=0, salient_bits=0, channel_metric=0) -> VidkvParams:
     if softmax_scale is None:
         softmax_scale = 1.0 / math.sqrt(head_dim)
     return VidkvParams(n_layers, batch, n_kv_heads, n_q_heads, head_dim, group, t_quant, n_anom,
-                       use_fft, n_salient, gamma, softmax_scale, t_capacity, salient_bits)
+                       use_fft, n_salient, gamma, softmax_scale, t_capacity, salient_bits, channel_metric)
 
 
 def status_string(status: int) -> str:

@@ -170,6 +170,94 @@ __global__ __launch_bounds__(1024) void k_select_kernel(const _Float16* __restri
   }
 }
 
+// ---------------------------------------------------------------------------
+// The two other channel metrics of Sec. 3.2 (1), both in float64 so that the
+// ranking does not depend on the summation order beyond the last bits:
+//   variance   sigma^2 = mean(x^2) - mean(x)^2 over all tokens of the channel
+//   outliers   N = #{ t : |x_t| > M * mean|x| },  M = 3
+// k_metric_kernel<MODE> writes per (head, chunk) partials double [2][128]:
+//   MODE 0: sum x, sum x^2      MODE 1: sum |x|, 0      MODE 2: count(|x| > thr), 0
+// grid (range_chunks, nheads), block 256: thread (row = tid / 16, col = tid % 16)
+// takes 8 channels of rows row, row + 16, ... of its chunk.
+// ---------------------------------------------------------------------------
+template <int MODE>
+__global__ __launch_bounds__(256) void k_metric_kernel(const u32x4* __restrict__ K, int T,
+                                                       int chunks, const double* __restrict__ thr,
+                                                       double* __restrict__ part) {
+  const int chunk = blockIdx.x;
+  const long long hd = blockIdx.y;
+  const int tid = threadIdx.x, col = tid & 15, row = tid >> 4;
+  const int t1 = min(T, (chunk + 1) * RANGE_CHUNK);
+  const u32x4* base = K + (hd * T) * 16 + col;
+  double a[8], b[8], th[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    a[e] = 0.0; b[e] = 0.0;
+    th[e] = MODE == 2 ? thr[hd * D + 8 * col + e] : 0.0;
+  }
+  for (int t = chunk * RANGE_CHUNK + row; t < t1; t += 16) {
+    U4H x;
+    x.u = base[(long long)t * 16];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const double v = (double)(float)x.e[e];
+      if (MODE == 0) { a[e] += v; b[e] = fma(v, v, b[e]); }
+      if (MODE == 1) a[e] += fabs(v);
+      if (MODE == 2) a[e] += fabs(v) > th[e] ? 1.0 : 0.0;
+    }
+  }
+  __shared__ double sa[16][D], sb[16][D];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) { sa[row][8 * col + e] = a[e]; sb[row][8 * col + e] = b[e]; }
+  __syncthreads();
+  if (tid < D) {
+    double x = 0.0, y = 0.0;
+    for (int r = 0; r < 16; ++r) { x += sa[r][tid]; y += sb[r][tid]; }
+    double* o = part + ((hd * chunks + chunk) * 2) * D;
+    o[tid] = x;
+    o[D + tid] = y;
+  }
+}
+
+// Folds the partials of one head (chunks in ascending order).  MODE 1: writes the
+// outlier threshold M * mean|x| per channel.  MODE 0 / 2: ranks the channels by
+// variance / outlier count (ties to the lower channel) and writes PERM like
+// k_select_kernel.  grid nheads, block 128: thread = channel.
+template <int MODE>
+__global__ __launch_bounds__(128) void k_metric_select_kernel(const double* __restrict__ part,
+                                                              int chunks, int T, int n_a,
+                                                              double* __restrict__ thr,
+                                                              uint8_t* __restrict__ perm) {
+  const long long hd = blockIdx.x;
+  const int c = threadIdx.x;
+  double x = 0.0, y = 0.0;
+  for (int k = 0; k < chunks; ++k) {
+    x += part[((hd * chunks + k) * 2) * D + c];
+    y += part[((hd * chunks + k) * 2 + 1) * D + c];
+  }
+  if (MODE == 1) {
+    thr[hd * D + c] = 3.0 * (x / (double)T);
+    return;
+  }
+  const double mean = x / (double)T;
+  const double r = MODE == 0 ? y / (double)T - mean * mean : x;
+  __shared__ double R[D];
+  __shared__ int flag[D];
+  R[c] = r;
+  __syncthreads();
+  int rank = 0;
+  for (int j = 0; j < D; ++j) {
+    const double rj = R[j];
+    rank += (rj > r || (rj == r && j < c)) ? 1 : 0;
+  }
+  const int an = rank < n_a ? 1 : 0;
+  flag[c] = an;
+  __syncthreads();
+  int below = 0;
+  for (int j = 0; j < c; ++j) below += flag[j];
+  perm[hd * D + (an ? below : n_a + (c - below))] = (uint8_t)c;
+}
+
 // The per-group coding pass (Eq. 4 and Eq. 5) lives in quant_keys_mfma.hip.
 void launch_k_encode(const Geom& g, const EncodeSpan& sp, const void* K, uint8_t* packed,
                      bool use_fft, hipStream_t st);
@@ -181,9 +269,36 @@ hipError_t launch_quantize_keys(const Geom& g, const void* K, uint8_t* packed, v
   if (g.T == 0) return hipSuccess;
   _Float16* w = reinterpret_cast<_Float16*>(ws);
   dim3 gr1(g.range_chunks, (unsigned)g.nheads);
+  const u32x4* k4 = reinterpret_cast<const u32x4*>(K);
+  if (g.metric != 0) {
+    // variance / outlier count (the paper's ablation; Range is what it adopts): float64
+    // partials [nheads][chunks][2][128], then the thresholds [nheads][128]
+    double* part = reinterpret_cast<double*>(ws);
+    double* thr = part + (size_t)g.nheads * g.range_chunks * 2 * D;
+    dim3 gh((unsigned)g.nheads);
+    if (g.metric == 1) {
+      if (stages & 1u)
+        hipLaunchKernelGGL(k_metric_kernel<0>, gr1, dim3(256), 0, st, k4, g.T, g.range_chunks, thr, part);
+      if (stages & 2u)
+        hipLaunchKernelGGL(k_metric_select_kernel<0>, gh, dim3(128), 0, st, part, g.range_chunks, g.T,
+                           g.n_a, thr, packed + g.k_perm);
+    } else {
+      if (stages & 1u) {
+        hipLaunchKernelGGL(k_metric_kernel<1>, gr1, dim3(256), 0, st, k4, g.T, g.range_chunks, thr, part);
+        hipLaunchKernelGGL(k_metric_select_kernel<1>, gh, dim3(128), 0, st, part, g.range_chunks, g.T,
+                           g.n_a, thr, packed + g.k_perm);
+        hipLaunchKernelGGL(k_metric_kernel<2>, gr1, dim3(256), 0, st, k4, g.T, g.range_chunks, thr, part);
+      }
+      if (stages & 2u)
+        hipLaunchKernelGGL(k_metric_select_kernel<2>, gh, dim3(128), 0, st, part, g.range_chunks, g.T,
+                           g.n_a, thr, packed + g.k_perm);
+    }
+    if (stages & 4u)
+      launch_k_encode(g, EncodeSpan{g.T, g.ng, 0, g.nheads, 0}, K, packed, g.use_fft, st);
+    return hipGetLastError();
+  }
   if (stages & 1u)
-    hipLaunchKernelGGL(k_range_kernel, gr1, dim3(256), 0, st, reinterpret_cast<const u32x4*>(K),
-                       g.T, g.range_chunks, w);
+    hipLaunchKernelGGL(k_range_kernel, gr1, dim3(256), 0, st, k4, g.T, g.range_chunks, w);
   if (stages & 2u)
     hipLaunchKernelGGL(k_select_kernel, dim3((unsigned)g.nheads), dim3(1024), 0, st, w,
                        g.range_chunks, g.n_a, packed + g.k_perm);

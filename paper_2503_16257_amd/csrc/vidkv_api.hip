@@ -25,6 +25,8 @@ hipError_t launch_saliency(const void* Xv, const void* Xt, int B, int Tv, int Nt
                            float* scores, float* tsum, hipStream_t st);
 
 static size_t ws_keys(const Geom& g) {
+  if (g.metric != 0)     // float64 partials and thresholds of the variance / outlier metrics
+    return align256(((size_t)g.nheads * g.range_chunks * 2 + (size_t)g.nheads) * D * sizeof(double)) + 256;
   return align256((size_t)g.nheads * g.range_chunks * 2 * D * sizeof(_Float16)) + 256;
 }
 static size_t ws_values(const Geom& g) { return values_ws_bytes(g); }

@@ -46,6 +46,7 @@ union U4H {
 struct Geom {
   int L, B, H, Hq, rep, T, ng, n_a, n_n, n_s;
   int Tcap, ngc;                   // capacity in tokens / groups: every per-head stride uses ngc
+  int metric;                      // channel ranking: 0 range, 1 variance, 2 outlier count
   bool use_fft;                    // normal key channels: Eq. 5 (true) or Eq. 4 at 1 bit (false)
   int sal_bits, npg;               // protected rows: 16 = fp16, 2 = Eq. 4 records; groups of 32 rows
   long long nheads;                // L*B*H
@@ -81,12 +82,14 @@ inline bool make_geom(const vidkv_params* p, Geom* g) {
   if (p->n_salient < 0 || p->n_salient > p->t_quant) return false;
   if (p->t_capacity != 0 && (p->t_capacity < p->t_quant || p->t_capacity % G)) return false;
   if (p->salient_bits != 0 && p->salient_bits != 16 && p->salient_bits != 2) return false;
+  if (p->channel_metric < 0 || p->channel_metric > 2) return false;
   g->L = p->n_layers; g->B = p->batch; g->H = p->n_kv_heads; g->Hq = p->n_q_heads;
   g->rep = g->Hq / g->H;
   g->T = p->t_quant; g->ng = g->T / G;
   g->Tcap = p->t_capacity ? p->t_capacity : p->t_quant; g->ngc = g->Tcap / G;
   g->n_a = p->n_anom; g->n_n = D - g->n_a; g->n_s = p->n_salient;
   g->use_fft = p->use_fft == 1;
+  g->metric = p->channel_metric;
   g->sal_bits = p->salient_bits == 2 ? 2 : 16;
   g->npg = (g->n_s + G - 1) / G;
   g->nheads = (long long)g->L * g->B * g->H;

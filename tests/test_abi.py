@@ -56,7 +56,7 @@ def test_stored_bits_per_element():
 def test_invalid_params_give_zero_sizes():
     bad = [
         dict(n_anom=7), dict(n_anom=136), dict(t_quant=33), dict(t_quant=-32), dict(head_dim=64),
-        dict(group=64), dict(n_q_heads=5), dict(n_q_heads=36), dict(use_fft=2),
+        dict(group=64), dict(n_q_heads=5), dict(n_q_heads=36), dict(use_fft=2), dict(channel_metric=3), dict(channel_metric=-1),
         dict(n_salient=65), dict(n_salient=-1), dict(n_layers=0), dict(batch=0), dict(n_kv_heads=0),
     ]
     for kw in bad:
@@ -140,6 +140,8 @@ def test_entry_points_refuse_bad_arguments_before_launch():
     assert vk.packed_values_bytes(vk.make_params(1, 2, 4, 28, 640, 16, 70, salient_bits=16)) == \
         LY.value_sections(1, 2, 4, 640, 70)["total"]
     assert vk.packed_values_bytes(vk.make_params(1, 2, 4, 28, 640, 16, 70, salient_bits=4)) == 0
+    var = vk.make_params(1, 2, 4, 28, 6400, 16, 0, channel_metric=1)
+    assert vk.workspace_bytes(var, 0) >= (8 * 13 * 2 + 8) * 128 * 8
     short = vk.make_params(1, 1, 4, 28, 64, 16, 4, t_capacity=32)
     assert vk.packed_keys_bytes(short) == 0
     odd = vk.make_params(1, 1, 4, 28, 64, 16, 4, t_capacity=100)

@@ -530,3 +530,28 @@ def test_standard_one_bit_quantizer_closed_forms():
     err_fft = ((Kd - O.dequantize_keys_head(a))[:, a["norm"]] ** 2).mean()
     err_std = ((Kd - Kb)[:, b["norm"]] ** 2).mean()
     assert err_std > 3 * err_fft
+
+
+def test_variance_and_outlier_metrics_closed_forms():
+    """The two other channel metrics of Sec. 3.2 (1): numpy's variance and a brute-force count;
+    on the synthetic keys all three metrics find the planted heavy-tailed channels."""
+    rng = np.random.default_rng(51)
+    K = _f16(rng.standard_normal((640, 128)) * rng.uniform(0.5, 2.0, 128) + rng.standard_normal(128))
+    np.testing.assert_allclose(O.key_channel_variance(K), K.astype(np.float64).var(axis=0), rtol=1e-12)
+    n = O.key_channel_outliers(K)
+    for c in (0, 17, 127):
+        a = [abs(float(v)) for v in K[:, c]]
+        m = sum(a) / len(a)
+        assert n[c] == sum(1 for v in a if v > 3 * m)
+    # a constant channel has no spread by any metric; a two-valued one has a known variance
+    K2 = K.copy(); K2[:, 5] = np.float16(1.5); K2[::2, 9] = np.float16(2.0); K2[1::2, 9] = np.float16(-2.0)
+    assert O.key_channel_variance(K2)[5] == 0 and O.key_channel_outliers(K2)[5] == 0
+    assert O.key_channel_variance(K2)[9] == 4.0 and O.key_channel_outliers(K2)[9] == 0
+    w = synth.WORKLOADS["c2_layer"]
+    Kh = synth.key_head(w, 1)
+    planted = set(synth.outlier_channels(w, 1).tolist())
+    for metric in (0, 1, 2):
+        rec = O.quantize_keys_head(Kh[:2048], 16, metric=metric)
+        assert planted <= set(rec["anom"].tolist()), metric
+    assert not np.array_equal(O.quantize_keys_head(Kh[:2048], 64, metric=1)["perm"],
+                              O.quantize_keys_head(Kh[:2048], 64, metric=2)["perm"])

@@ -46,6 +46,11 @@ def lib() -> C.CDLL:
         if not os.path.exists(LIB_PATH):
             raise RuntimeError(
                 f"{LIB_PATH} is missing: build it with `python -m paper_2503_16257_amd.build`")
+        # PyTorch ships its own HIP runtime; it must be in the process before this library is
+        # loaded, so that both resolve to that one copy.  Loaded the other way round the
+        # library registers its kernels with a second runtime, and every launch on a torch
+        # stream fails.
+        import torch  # noqa: F401
         L = C.CDLL(LIB_PATH)
         PP = C.POINTER(VidkvParams)
         vp, sz, i32 = C.c_void_p, C.c_size_t, C.c_int32

@@ -101,7 +101,8 @@ size_t vidkv_workspace_bytes(const vidkv_params *params, int which);
  * and 32-token group, round-half-even) and the others with Eq. 5: a 32-point
  * DFT along the tokens of each group, one sign bit for each of the 17 real and
  * 15 imaginary independent coefficients, and the mean |Re|, mean |Im| over the
- * 32 bins as fp16 scales.
+ * 32 bins as fp16 scales.  `channel_metric` and `use_fft` in the parameters
+ * select the paper's other ranking metrics and its non-FFT 1-bit code.
  *   K_dev        in : [L, B, Hkv, Tq, 128] fp16
  *   packed_K_dev out: >= vidkv_packed_keys_bytes(params) bytes
  *   workspace_dev   : >= vidkv_workspace_bytes(params, 0) bytes, scratch     */

@@ -21,7 +21,10 @@
  *    failed check returns a status and launches nothing.  A launch failure
  *    returns VIDKV_EHIP.  Nothing aborts or throws across this boundary.
  *  - Tensors are dense, row-major, fp16 (IEEE binary16) unless stated.
- *    Inputs must be finite; non-finite inputs give unspecified codes.
+ *    Inputs must be finite; non-finite inputs give unspecified codes.  All
+ *    stored scales are fp16: a 32-token group of keys whose mean spectral
+ *    magnitude (Eq. 5) exceeds 65504 - values of order 10^4 with a common
+ *    sign - overflows its scale, with unspecified results for that group.
  *  - Shapes: L = n_layers, B = batch, Hkv = n_kv_heads, Hq = n_q_heads
  *    (Hq % Hkv == 0, Hq / Hkv <= 8; query head h reads KV head h / (Hq/Hkv)),
  *    D = head_dim = 128, G = group = 32, Tq = t_quant (multiple of 32).

@@ -28,6 +28,10 @@
  *  - Shapes: L = n_layers, B = batch, Hkv = n_kv_heads, Hq = n_q_heads
  *    (Hq % Hkv == 0, Hq / Hkv <= 8; query head h reads KV head h / (Hq/Hkv)),
  *    D = head_dim = 128, G = group = 32, Tq = t_quant (multiple of 32).
+ *    One quantize call covers at most 65535 (layer, sequence, KV head)
+ *    triples, one decode or flush call at most 65535 sequences (and
+ *    sequences x KV heads for a flush); larger shapes return VIDKV_ESHAPE
+ *    and are to be split over several calls by the caller.
  *  - The packed buffers are opaque to the caller; their byte sizes come from
  *    the vidkv_packed_*_bytes functions.  Packed buffers and workspaces must
  *    be 256-byte aligned; fp16 tensors and the saliency scores 16-byte

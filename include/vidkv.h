@@ -31,7 +31,8 @@
  *    One quantize call covers at most 65535 (layer, sequence, KV head)
  *    triples, one decode or flush call at most 65535 sequences (and
  *    sequences x KV heads for a flush); larger shapes return VIDKV_ESHAPE
- *    and are to be split over several calls by the caller.
+ *    and are to be split by the caller, e.g. one set of packed buffers (and
+ *    one params with n_layers = 1) per layer.
  *  - The packed buffers are opaque to the caller; their byte sizes come from
  *    the vidkv_packed_*_bytes functions.  Packed buffers and workspaces must
  *    be 256-byte aligned; fp16 tensors and the saliency scores 16-byte

@@ -21,7 +21,7 @@ Conventions
 Readings of the paper taken here (each is listed with its alternative in the
 design notes of the repository):
   - the FFT runs along the token axis, one 32-point transform per channel and
-    group (Sec. 3.2 (2): "from the time domain to the frequency domain");
+    group (Sec. 3.2 (2) transforms each channel's sequence over time);
   - Eq. 5's code is the sign bit, bit = [coef >= 0], and dequantizes to the
     symmetric levels +-s (the formula as printed would give {0, 2});
   - the real and imaginary parts are quantized as separate real channels
@@ -31,7 +31,11 @@ design notes of the repository):
   - ternary values dequantize to s * code with s = Mean(|V|) (Alg. 2 names no
     other scale);
   - protected tokens keep their positions: they are left out of the group
-    mean, coded 0 and stored verbatim in fp16.
+    mean, coded 0 and stored verbatim in fp16, or (stp_quant_rows) at 2 bits;
+  - a full residual block is coded on its own with the prefill's channel
+    split (quantize_keys_block); the non-FFT 1-bit code is Eq. 4 with n = 1;
+    the saliency scores of Eq. 7 are summed over the text tokens.
+Every function here is pinned by tests/test_oracle_pins.py; none is "parity unpinned".
 """
 from __future__ import annotations
 

@@ -57,9 +57,9 @@ def algorithmic_bytes(w):
     }
 
 
-def cpu_baseline(w, budget_tokens=196000):
-    """The oracle, as it stands, on a bounded sample: one KV head, first
-    `budget_tokens` tokens of the workload, all query heads of that KV head."""
+def cpu_baseline(w, budget_tokens=196000, budget_heads=4):
+    """The oracle, as it stands, on a bounded sample: the first `budget_heads` KV heads of
+    layer 0, sequence 0, first `budget_tokens` tokens, all query heads of those KV heads."""
     import numpy as np
     from oracle import vidkv_oracle as O
     from paper_2503_16257_amd import synth
@@ -69,29 +69,39 @@ def cpu_baseline(w, budget_tokens=196000):
     except Exception:
         cores = os.cpu_count() or 1
     T = min(w.T, budget_tokens) // 32 * 32
-    K = synth.key_head(w, 0)[:T]
-    V = synth.value_head(w, 0)[:T]
+    nh = min(w.Hkv, budget_heads)
     n_s = (w.n_salient * T) // max(w.T, 1)
     sc = synth.saliency(w)[0, :T]
     rep = w.Hq // w.Hkv
-    q = synth.query(w, 0)[0, :rep]
-    t0 = time.perf_counter()
-    rec = O.quantize_keys_head(K, w.n_anom)
-    sal = O.select_salient_tokens(sc, n_s)
-    qv = O.ternary_quant(V, sal, float(np.float32(0.7)))
-    t1 = time.perf_counter()
-    Kd = O.dequantize_keys_head(rec)
-    Vd = O.ternary_dequant(qv["codes"], qv["s16"], sal, qv["rows"])
-    for h in range(rep):
-        O.attention_single_query(q[h], Kd, Vd, 1.0 / np.sqrt(128.0))
-    t2 = time.perf_counter()
-    # the sample is 1 of Hkv KV heads of one layer of one sequence
-    tok_equiv = T / w.Hkv
+    t_quant = t_attn = 0.0
+    done = 0
+    for h in range(nh):
+        if t_quant + t_attn > 15.0:          # keep the leg bounded on a slow host
+            break
+        done += 1
+        K = synth.key_head(w, h)[:T]
+        V = synth.value_head(w, h)[:T]
+        q = synth.query(w, 0)[0, h * rep:(h + 1) * rep]
+        t0 = time.perf_counter()
+        rec = O.quantize_keys_head(K, w.n_anom)
+        sal = O.select_salient_tokens(sc, n_s)
+        qv = O.ternary_quant(V, sal, float(np.float32(0.7)))
+        t1 = time.perf_counter()
+        Kd = O.dequantize_keys_head(rec)
+        Vd = O.ternary_dequant(qv["codes"], qv["s16"], sal, qv["rows"])
+        for j in range(rep):
+            O.attention_single_query(q[j], Kd, Vd, 1.0 / np.sqrt(128.0))
+        t2 = time.perf_counter()
+        t_quant += t1 - t0
+        t_attn += t2 - t1
+    # the sample is `done` of the Hkv KV heads of one layer of one sequence
+    nh = done
+    tok_equiv = T * nh / w.Hkv
     return {
-        "value": tok_equiv / (t2 - t0), "unit": "visual tokens/s", "cores": int(cores),
+        "value": tok_equiv / (t_quant + t_attn), "unit": "visual tokens/s", "cores": int(cores),
         "kind": "oracle",
-        "sample": f"1 KV head x {T} tokens of {w.name} (quantize K+V, select, 1 decode step); "
-                  f"quantize {t1 - t0:.2f} s, attention {t2 - t1:.2f} s",
+        "sample": f"{nh} KV head(s) x {T} tokens of {w.name} (quantize K+V, select, 1 decode step); "
+                  f"quantize {t_quant:.2f} s, attention {t_attn:.2f} s",
     }
 
 

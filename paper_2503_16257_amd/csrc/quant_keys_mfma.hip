@@ -286,8 +286,8 @@ __global__ __launch_bounds__(256) void k_encode_mfma_kernel(const u32x4* __restr
     // ---- the finished record: LDS -> global, 16 bytes per lane
     u32x4* dst = reinterpret_cast<u32x4*>(rec_out + (hd * ngc + g_out0 + g) * (long long)krec);
     const int nch = krec >> 4;
-    if (lane < nch) dst[lane] = recbuf[wave][lane];
-    if (lane + 64 < nch) dst[lane + 64] = recbuf[wave][lane + 64];
+    if (lane < nch) __builtin_nontemporal_store(recbuf[wave][lane], dst + lane);
+    if (lane + 64 < nch) __builtin_nontemporal_store(recbuf[wave][lane + 64], dst + lane + 64);
   }
 }
 

@@ -8,7 +8,7 @@
 // reads its channel (16 m + x16) at its 8 token slots as 4 packed fp16 pairs -
 // the same (lane group kb, slot) token order as the trit words of the record,
 // so a lane assembles its 16 bytes of the record in registers and stores them
-// straight to global memory.  Work is done on packed halves:
+// straight to global memory (streaming stores: the record is not read again here).  Work is done on packed halves:
 //   sum |v|      : v_dot2_f32_f16(|v| pair, keep pair, acc)  (exact products, fp32 sum)
 //   |v| > alpha  : fp16 bit patterns of non-negative values order like integers,
 //                  so with thr = alpha rounded toward zero to fp16,
@@ -137,11 +137,11 @@ __global__ __launch_bounds__(256) void v_encode_wave_kernel(const u32x4* __restr
     uint8_t* rec = rec_out + (hd * ngc + g_out0 + g) * (long long)VREC;
     u32x4 wv;
     wv[0] = words[0]; wv[1] = words[1]; wv[2] = words[2]; wv[3] = words[3];
-    reinterpret_cast<u32x4*>(rec)[lane] = wv;                   // word (kb, x16, mp) at byte 16 lane + 4 mp
+    __builtin_nontemporal_store(wv, reinterpret_cast<u32x4*>(rec) + lane);                 // word (kb, x16, mp) at byte 16 lane + 4 mp
     if (kb == 0) {
       u32x4 sv;
       sv[0] = sc16[0]; sv[1] = sc16[1]; sv[2] = sc16[2]; sv[3] = sc16[3];
-      reinterpret_cast<u32x4*>(rec + 1024)[x16] = sv;           // fp16 [r = x16][m]
+      __builtin_nontemporal_store(sv, reinterpret_cast<u32x4*>(rec + 1024) + x16);         // fp16 [r = x16][m]
     }
     // protected rows, verbatim, to ROWS[rank + order inside the group] (not when they are
     // kept at 2 bits: a pass of its own codes them)
@@ -150,8 +150,9 @@ __global__ __launch_bounds__(256) void v_encode_wave_kernel(const u32x4* __restr
       const int t = __ffs(w) - 1;
       w &= w - 1;
       if (lane < 16)
-        rows_out[(hd * n_s + r) * 16 + lane] =
-            *reinterpret_cast<const u32x4*>(reinterpret_cast<const uint8_t*>(&tile4[wave][0]) + t * VENC_ROW + lane * 16);
+        __builtin_nontemporal_store(
+            *reinterpret_cast<const u32x4*>(reinterpret_cast<const uint8_t*>(&tile4[wave][0]) + t * VENC_ROW + lane * 16),
+            rows_out + (hd * n_s + r) * 16 + lane);
       ++r;
     }
   }

@@ -155,13 +155,13 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a) {
     for (int grp = 0; grp < 2; ++grp) {
       const int g = min(2 * p + grp, a.ng - 1);
       const u32x4* ks = reinterpret_cast<const u32x4*>(krec_base + (long long)g * KREC);
-      kpre[grp][0] = ks[lane < KCH ? lane : 0];
-      kpre[grp][1] = ks[lane + 64 < KCH ? lane + 64 : 0];
+      kpre[grp][0] = __builtin_nontemporal_load(ks + (lane < KCH ? lane : 0));
+      kpre[grp][1] = __builtin_nontemporal_load(ks + (lane + 64 < KCH ? lane + 64 : 0));
       const u32x4* vs = reinterpret_cast<const u32x4*>(vrec_base + (long long)g * VREC);
-      vwpre[grp] = vs[lane];
+      vwpre[grp] = __builtin_nontemporal_load(vs + lane);
     }
     const int gs = min(2 * p + (kb >> 1), a.ng - 1);
-    vspre = reinterpret_cast<const u32x4*>(vrec_base + (long long)gs * VREC)[64 + x16];
+    vspre = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(vrec_base + (long long)gs * VREC) + 64 + x16);
   };
   // Protected rows are fetched one pair ahead, their masks two pairs ahead.
   // The rows of one pair are consecutive in ROWS (rank grows with the token).
@@ -184,7 +184,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a) {
       const uint8_t* rec = reinterpret_cast<const uint8_t*>(a.vrows) + (hd * a.npg + (r >> 5)) * (long long)PREC;
       return rec[(r & 31) * 32 + (lane >> 1)];
     }
-    return *(reinterpret_cast<const uint32_t*>(a.vrows + (hd * a.n_s + r) * D) + lane);
+    return __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(a.vrows + (hd * a.n_s + r) * D) + lane);
   };
   auto issue_rows = [&](uint32_t s0, uint32_t s1, uint32_t rk, uint32_t* rows) {
     const int cnt = __popc(s0) + __popc(s1);

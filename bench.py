@@ -33,8 +33,8 @@ BYTES_V_PER_ELEM = 0.2625      # 1.6-bit trits + one fp16 scale per 32 elements
 # summarized in profiles/c4_long_hbm_traffic.md; a workload that was not
 # counted reports null.
 MEASURED_TRAFFIC_BYTES = {
-    "c4_long": {"k_range": 200.75e6 + 0.78e6, "k_encode": 200.87e6 + 26.66e6,
-                "v_encode": 201.59e6 + 41.40e6, "attn_partial": 68.49e6 + 1.86e6},
+    "c4_long": {"k_range": 200.75e6 + 0.78e6, "k_encode": 200.84e6 + 27.09e6,
+                "v_encode": 201.59e6 + 41.40e6, "attn_partial": 68.61e6 + 1.86e6},
 }
 
 

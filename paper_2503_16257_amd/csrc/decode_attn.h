@@ -16,12 +16,13 @@ struct AttnArgs {
   const _Float16* ktail;     // [B, H, cap, 128]
   const _Float16* vtail;
   const int32_t* tail_len;   // [B] or NULL
-  float* part;               // [(nsplit+1), B, Hq, 130]
+  float* part;               // [nsplit + tail splits, B, Hq, 130]
   int layer, B, H, Hq, rep, ng, n_a, n_n, n_s, krec_bytes, cap, nsplit, gps;
   int ngc;                   // groups of capacity: stride of the per-head record arrays
   int use_fft;               // normal key channels coded by Eq. 5 (1) or by Eq. 4 at 1 bit (0)
   int sal_bits, npg;         // protected rows kept as fp16 (16) or Eq. 4 codes (2); groups of 32 rows
   int split0;                // added to blockIdx.x (tail-only launches start at nsplit)
+  int tail_per;              // 32-token steps of the residual buffer per tail split
   float scale2;              // softmax scale * log2(e): scores live in the exp2 domain
 };
 

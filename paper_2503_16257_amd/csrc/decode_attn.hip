@@ -46,8 +46,9 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
   float m_run = -INFINITY, l_run = 0.0f;             // valid in threads with h_s < R
   float acc[4] = {0.f, 0.f, 0.f, 0.f};
 
-  const bool is_tail = (split == a.nsplit);
-  int n_iter, g_begin = 0, tl = 0;
+  // splits nsplit .. nsplit + ntail - 1 share the residual tokens, 32 * tail_per at a time
+  const bool is_tail = (split >= a.nsplit);
+  int n_iter, g_begin = 0, tl = 0, it0 = 0;
   if (!is_tail) {
     g_begin = split * a.gps;
     const int g_end = min(a.ng, g_begin + a.gps);
@@ -55,7 +56,8 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
   } else {
     tl = a.tail_len ? a.tail_len[b] : 0;
     tl = min(max(tl, 0), a.cap);
-    n_iter = (tl + 31) / 32;
+    it0 = (split - a.nsplit) * a.tail_per;
+    n_iter = max(0, min((tl + 31) / 32, it0 + a.tail_per) - it0);
   }
 
   const uint16_t* kbits = reinterpret_cast<const uint16_t*>(krec4) + 6 * a.n_a;
@@ -126,7 +128,7 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
       }
     } else {
       // ---- residual tokens: plain fp16 rows
-      const int tok = it * 32 + t_s;
+      const int tok = (it0 + it) * 32 + t_s;
       if (h_s < R && tok < tl) {
         const u32x4* row = reinterpret_cast<const u32x4*>(
             a.ktail + (((long long)b * a.H + kvh) * a.cap + tok) * D);
@@ -193,14 +195,14 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
         ++r;
       }
     } else {
-      const int nt = min(32, tl - it * 32);
+      const int nt = min(32, tl - (it0 + it) * 32);
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const int h = half_o + 2 * i;
         if (h < R) acc[i] *= Alpha[h];
       }
       for (int t = 0; t < nt; ++t) {
-        const float v = (float)a.vtail[(((long long)b * a.H + kvh) * a.cap + it * 32 + t) * D + c_o];
+        const float v = (float)a.vtail[(((long long)b * a.H + kvh) * a.cap + (it0 + it) * 32 + t) * D + c_o];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
           const int h = half_o + 2 * i;
@@ -321,7 +323,11 @@ hipError_t launch_decode_attention(const Geom& g, int layer, float scale, const 
   const bool mfma = a.nsplit > 0 && attn_mfma_supported(g.n_a);
   // with the MFMA kernel the residual-token block is a launch of its own and is
   // skipped when there is no residual buffer
-  const int nparts = (mfma && !has_tail) ? a.nsplit : a.nsplit + 1;
+  // residual tokens: up to ATTN_TAIL_SPLITS workgroups per (sequence, KV head)
+  const int tail_iters = has_tail ? (cap + 31) / 32 : 0;
+  const int ntail = has_tail ? (tail_iters < ATTN_TAIL_SPLITS ? tail_iters : ATTN_TAIL_SPLITS) : (mfma ? 0 : 1);
+  a.tail_per = ntail > 0 && tail_iters > 0 ? (tail_iters + ntail - 1) / ntail : 0;
+  const int nparts = a.nsplit + ntail;
   if (stages & 1u) {
     if (mfma) {
       const int npairs = (g.ng + 1) / 2;
@@ -329,11 +335,11 @@ hipError_t launch_decode_attention(const Geom& g, int layer, float scale, const 
       launch_attn_mfma(a, dim3(a.nsplit, g.H, g.B), st);
       if (has_tail) {
         a.split0 = a.nsplit;
-        hipLaunchKernelGGL(attn_partial_kernel, dim3(1, g.H, g.B), dim3(256), 0, st, a);
+        hipLaunchKernelGGL(attn_partial_kernel, dim3(ntail, g.H, g.B), dim3(256), 0, st, a);
       }
     } else {
       a.gps = a.nsplit ? (g.ng + a.nsplit - 1) / a.nsplit : 0;
-      hipLaunchKernelGGL(attn_partial_kernel, dim3(a.nsplit + 1, g.H, g.B), dim3(256), 0, st, a);
+      hipLaunchKernelGGL(attn_partial_kernel, dim3(a.nsplit + ntail, g.H, g.B), dim3(256), 0, st, a);
     }
   }
   if (stages & 2u)

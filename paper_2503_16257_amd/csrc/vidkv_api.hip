@@ -37,7 +37,7 @@ static size_t ws_attn(const Geom& g) {
   c.T = g.Tcap;
   c.ng = g.ngc;
   const int ns = attn_num_splits(c) > attn_num_splits(g) ? attn_num_splits(c) : attn_num_splits(g);
-  return align256((size_t)(ns + 1) * g.B * g.Hq * (D + 2) * sizeof(float)) + 256;
+  return align256((size_t)(ns + ATTN_TAIL_SPLITS) * g.B * g.Hq * (D + 2) * sizeof(float)) + 256;
 }
 static bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 

@@ -32,6 +32,7 @@ constexpr int VREC = 1280;         // bytes of one value record
 constexpr int PREC = 1536;         // bytes of one record of 32 protected rows at 2 bits (Eq. 4)
 constexpr int RANGE_CHUNK = 512;   // tokens per workgroup in the key range pass
 constexpr int MAX_REP = 8;         // query heads per KV head
+constexpr int ATTN_TAIL_SPLITS = 8; // most workgroups that share one head's residual tokens in attention
 
 typedef _Float16 h2 __attribute__((ext_vector_type(2)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));

@@ -201,12 +201,21 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
         const int h = half_o + 2 * i;
         if (h < R) acc[i] *= Alpha[h];
       }
-      for (int t = 0; t < nt; ++t) {
-        const float v = (float)a.vtail[(((long long)b * a.H + kvh) * a.cap + (it0 + it) * 32 + t) * D + c_o];
+      // 8 rows in flight per thread (a row past the end repeats the last one and is not used)
+      const _Float16* vcol = a.vtail + (((long long)b * a.H + kvh) * a.cap + (it0 + it) * 32) * D + c_o;
+      for (int t0 = 0; t0 < nt; t0 += 8) {
+        float v[8];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const int h = half_o + 2 * i;
-          if (h < R) acc[i] += P[h][t] * v;
+        for (int u = 0; u < 8; ++u) v[u] = (float)vcol[(long long)min(t0 + u, nt - 1) * D];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          if (t0 + u < nt) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              const int h = half_o + 2 * i;
+              if (h < R) acc[i] += P[h][t0 + u] * v[u];
+            }
+          }
         }
       }
     }
@@ -221,6 +230,95 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
       float* o = a.part + (((long long)split * a.B + b) * a.Hq + kvh * R + h) * PART_STRIDE;
       o[c_o] = acc[i];
     }
+  }
+  if (h_s < R && t_s == 0) {
+    float* o = a.part + (((long long)split * a.B + b) * a.Hq + kvh * R + h_s) * PART_STRIDE;
+    o[D] = m_run;
+    o[D + 1] = l_run;
+  }
+}
+
+// The fp16 residual tokens (Alg. 1's X_Kr, X_Vr): one workgroup = one (tail split, KV head,
+// sequence); split ts takes the 32-token steps ts * tail_per .. of the buffer and writes its
+// partial (o, m, l) as split index nsplit + ts.  Thread roles: scores (token = tid % 32,
+// head = tid / 32), output (channel = tid % 128, heads tid / 128 + 2 i).
+__global__ __launch_bounds__(256) void attn_tail_kernel(AttnArgs a) {
+  const int ts = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
+  const int split = a.nsplit + ts;
+  const int tid = threadIdx.x;
+  const int R = a.rep;
+  __shared__ float t_q[MAX_REP][D];
+  __shared__ float t_P[MAX_REP][32];
+  __shared__ float t_alpha[MAX_REP];
+  for (int i = tid; i < R * D; i += 256)
+    t_q[i >> 7][i & 127] = (float)a.q[((long long)b * a.Hq + kvh * R + (i >> 7)) * D + (i & 127)];
+  const int t_s = tid & 31, h_s = tid >> 5;
+  const int c_o = tid & 127, half_o = tid >> 7;
+  float m_run = -INFINITY, l_run = 0.0f;
+  float acc[4] = {0.f, 0.f, 0.f, 0.f};
+  int tl = a.tail_len ? a.tail_len[b] : 0;
+  tl = min(max(tl, 0), a.cap);
+  const int it0 = ts * a.tail_per;
+  const int n_iter = max(0, min((tl + 31) / 32, it0 + a.tail_per) - it0);
+  const long long head_row0 = ((long long)b * a.H + kvh) * a.cap;
+  for (int it = 0; it < n_iter; ++it) {
+    const int tok0 = (it0 + it) * 32;
+    const int nt = min(32, tl - tok0);
+    // everything this step reads is requested up front: my key row (16 pieces) and my
+    // channel of the 32 value rows (a row past the end repeats the last one and is not used)
+    const bool scorer = h_s < R && t_s < nt;
+    U4H kr[16];
+    if (scorer) {
+      const u32x4* row = reinterpret_cast<const u32x4*>(a.ktail + (head_row0 + tok0 + t_s) * D);
+#pragma unroll
+      for (int i = 0; i < 16; ++i) kr[i].u = row[i];
+    }
+    const _Float16* vcol = a.vtail + (head_row0 + tok0) * D + c_o;
+    _Float16 vv[32];
+#pragma unroll
+    for (int u = 0; u < 32; ++u) vv[u] = vcol[(long long)min(u, nt - 1) * D];
+    if (it == 0) __syncthreads();                    // q is in LDS (its loads overlapped the above)
+    float score = -INFINITY;
+    if (scorer) {
+      float v = 0.0f;
+#pragma unroll
+      for (int i = 0; i < 16; ++i)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v += t_q[h_s][i * 8 + e] * (float)kr[i].e[e];
+      score = v * a.scale2;
+    }
+    if (h_s < R) {                                   // online softmax of this step (exp2 domain)
+      float mx = score;
+#pragma unroll
+      for (int d = 16; d >= 1; d >>= 1) mx = fmaxf(mx, __shfl_xor(mx, d, 32));
+      const float m_new = fmaxf(m_run, mx);
+      const float p = (score == -INFINITY) ? 0.0f : exp2f(score - m_new);
+      const float al = (m_run == -INFINITY) ? 0.0f : exp2f(m_run - m_new);
+      float ps = p;
+#pragma unroll
+      for (int d = 16; d >= 1; d >>= 1) ps += __shfl_xor(ps, d, 32);
+      l_run = l_run * al + ps;
+      m_run = m_new;
+      t_P[h_s][t_s] = p;
+      if (t_s == 0) t_alpha[h_s] = al;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int h = half_o + 2 * i;
+      if (h < R) {
+        float s_acc = acc[i] * t_alpha[h];
+#pragma unroll
+        for (int u = 0; u < 32; ++u) s_acc += t_P[h][u] * (float)vv[u];   // t_P is 0 past the end
+        acc[i] = s_acc;
+      }
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int h = half_o + 2 * i;
+    if (h < R) a.part[(((long long)split * a.B + b) * a.Hq + kvh * R + h) * PART_STRIDE + c_o] = acc[i];
   }
   if (h_s < R && t_s == 0) {
     float* o = a.part + (((long long)split * a.B + b) * a.Hq + kvh * R + h_s) * PART_STRIDE;
@@ -334,8 +432,7 @@ hipError_t launch_decode_attention(const Geom& g, int layer, float scale, const 
       a.gps = (npairs + a.nsplit - 1) / a.nsplit;          // pairs per split
       launch_attn_mfma(a, dim3(a.nsplit, g.H, g.B), st);
       if (has_tail) {
-        a.split0 = a.nsplit;
-        hipLaunchKernelGGL(attn_partial_kernel, dim3(ntail, g.H, g.B), dim3(256), 0, st, a);
+        hipLaunchKernelGGL(attn_tail_kernel, dim3(ntail, g.H, g.B), dim3(256), 0, st, a);
       }
     } else {
       a.gps = a.nsplit ? (g.ng + a.nsplit - 1) / a.nsplit : 0;

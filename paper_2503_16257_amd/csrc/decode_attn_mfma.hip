@@ -456,13 +456,47 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a) {
             osal[h][1] += ph * v1;
           }
         };
+        // fp16 rows go two at a time: (row A, row B) of one channel as a packed pair against
+        // the pair of their probabilities (rounded to nearest fp16: these rows carry the largest
+        // values, so a one-sided rounding would show in the output),
+        // one v_dot2_f32_f16 per (head, channel)
+        auto add_rows2 = [&](uint32_t bitsA, uint32_t bitsB) {
+          const int tA = __ffsll((long long)sm) - 1;
+          sm &= sm - 1;
+          const bool hasB = sm != 0;
+          const int tB = hasB ? __ffsll((long long)sm) - 1 : tA;
+          if (hasB) sm &= sm - 1; else bitsB = 0u;
+          const h2 c0 = bits_h2(__builtin_amdgcn_perm(bitsB, bitsA, 0x05040100u));   // channel 2 lane
+          const h2 c1 = bits_h2(__builtin_amdgcn_perm(bitsB, bitsA, 0x07060302u));   // channel 2 lane + 1
+          const float* pa = &pl[wave][tA & 31][8 * (tA >> 5)];
+          const float* pb = &pl[wave][tB & 31][8 * (tB >> 5)];
 #pragma unroll
-        for (int j = 0; j < NROW; ++j)
-          if (sm) add_row(rowcur[j], rkc + j);
-        uint32_t rk = rkc + NROW;                           // more than NROW rows: fetch on demand
-        while (sm) {
-          add_row(row_word(rk), rk);
-          ++rk;
+          for (int h = 0; h < 8; ++h) {
+            const h2 w = __builtin_convertvector(f2{pa[h], pb[h]}, h2);   // round to nearest
+            osal[h][0] = __builtin_amdgcn_fdot2(c0, w, osal[h][0], false);
+            osal[h][1] = __builtin_amdgcn_fdot2(c1, w, osal[h][1], false);
+          }
+        };
+        if (SAL == 1) {
+#pragma unroll
+          for (int j = 0; j < NROW; j += 2)
+            if (sm) add_rows2(rowcur[j], rowcur[j + 1]);
+          uint32_t rk = rkc + NROW;                         // more than NROW rows: fetch on demand
+          while (sm) {
+            const uint32_t ra = row_word(rk);
+            const uint32_t rb = (sm & (sm - 1)) ? row_word(rk + 1) : 0u;
+            add_rows2(ra, rb);
+            rk += 2;
+          }
+        } else {
+#pragma unroll
+          for (int j = 0; j < NROW; ++j)
+            if (sm) add_row(rowcur[j], rkc + j);
+          uint32_t rk = rkc + NROW;                         // more than NROW rows: fetch on demand
+          while (sm) {
+            add_row(row_word(rk), rk);
+            ++rk;
+          }
         }
       }
       sm0c = sm0n; sm1c = sm1n; rkc = rkn;

@@ -13,6 +13,7 @@ namespace vidkv {
 
 typedef _Float16 h8 __attribute__((ext_vector_type(8)));
 typedef float f4 __attribute__((ext_vector_type(4)));
+typedef float f2 __attribute__((ext_vector_type(2)));
 
 union Op {   // one MFMA operand
   h8 v;

@@ -379,6 +379,54 @@ __global__ __launch_bounds__(1024) void attn_merge_kernel(const float* __restric
   }
 }
 
+// The same merge for at most 8 * MAXU parts: every load of a thread is issued before the
+// first use (one round trip to memory instead of one per 32 parts and one for the maximum).
+// Thread (slice sl, channel c) owns parts sl, sl + 8, ...
+template <int MAXU>
+__global__ __launch_bounds__(1024) void attn_merge_small_kernel(const float* __restrict__ part,
+                                                                int nparts, int B, int Hq,
+                                                                _Float16* __restrict__ out) {
+  const int h = blockIdx.x, b = blockIdx.y;
+  const int c = threadIdx.x & 127, sl = threadIdx.x >> 7;
+  __shared__ float so[8][D];
+  __shared__ float sl_[8];
+  __shared__ float sM[8];
+  float mi[MAXU], oi[MAXU], li[MAXU];
+#pragma unroll
+  for (int u = 0; u < MAXU; ++u) {
+    const int i = sl + 8 * u;
+    const bool ok = i < nparts;
+    const float* p = part + (((long long)(ok ? i : 0) * B + b) * Hq + h) * PART_STRIDE;
+    mi[u] = ok ? p[D] : -INFINITY;
+    oi[u] = ok ? p[c] : 0.0f;
+    li[u] = ok ? p[D + 1] : 0.0f;
+  }
+  float M = mi[0];
+#pragma unroll
+  for (int u = 1; u < MAXU; ++u) M = fmaxf(M, mi[u]);
+  if (c == 0) sM[sl] = M;
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < 8; ++i) M = fmaxf(M, sM[i]);
+  float o = 0.0f, l = 0.0f;
+#pragma unroll
+  for (int u = 0; u < MAXU; ++u) {
+    const float w = mi[u] == -INFINITY ? 0.0f : exp2f(mi[u] - M);
+    if (w != 0.0f) {                       // an empty part's sums are never looked at
+      o += w * oi[u];
+      l += w * li[u];
+    }
+  }
+  so[sl][c] = o;
+  if (c == 0) sl_[sl] = l;
+  __syncthreads();
+  if (sl == 0) {
+#pragma unroll
+    for (int i = 1; i < 8; ++i) { o += so[i][c]; l += sl_[i]; }
+    out[((long long)b * Hq + h) * D + c] = (_Float16)(l > 0.0f ? o / l : 0.0f);
+  }
+}
+
 // Number of split-T workgroups per (sequence, KV head).
 int attn_num_splits(const Geom& g) {
   if (g.ng == 0) return 0;
@@ -439,9 +487,18 @@ hipError_t launch_decode_attention(const Geom& g, int layer, float scale, const 
       hipLaunchKernelGGL(attn_partial_kernel, dim3(a.nsplit + ntail, g.H, g.B), dim3(256), 0, st, a);
     }
   }
-  if (stages & 2u)
-    hipLaunchKernelGGL(attn_merge_kernel, dim3(g.Hq, g.B), dim3(1024), 0, st, a.part, nparts,
-                       g.B, g.Hq, reinterpret_cast<_Float16*>(out));
+  if (stages & 2u) {
+    _Float16* o16 = reinterpret_cast<_Float16*>(out);
+    if (nparts <= 16)
+      hipLaunchKernelGGL(attn_merge_small_kernel<2>, dim3(g.Hq, g.B), dim3(1024), 0, st, a.part,
+                         nparts, g.B, g.Hq, o16);
+    else if (nparts <= 136)
+      hipLaunchKernelGGL(attn_merge_small_kernel<17>, dim3(g.Hq, g.B), dim3(1024), 0, st, a.part,
+                         nparts, g.B, g.Hq, o16);
+    else
+      hipLaunchKernelGGL(attn_merge_kernel, dim3(g.Hq, g.B), dim3(1024), 0, st, a.part, nparts,
+                         g.B, g.Hq, o16);
+  }
   return hipGetLastError();
 }
 

@@ -87,24 +87,24 @@ __global__ __launch_bounds__(1024) void k_select_kernel(const _Float16* __restri
   const long long hd = blockIdx.x;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   // gather: thread (slice = tid / 16, col = tid % 16) folds 8 channels of the
-  // chunks slice, slice + 64, ... with 16-byte loads, 4 chunks in flight
+  // chunks slice, slice + 64, ... with 16-byte loads, 8 chunks in flight
   const int col = tid & 15, slice = tid >> 4;
   const u32x4* p4 = reinterpret_cast<const u32x4*>(ws + hd * chunks * 2 * D) + col;
   const _Float16 big = (_Float16)65504.0f;
   h2 mn[4], mx[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) { mn[i] = h2{big, big}; mx[i] = h2{-big, -big}; }
-  for (int k0 = slice; k0 < chunks; k0 += 256) {
-    U4H a[4], b[4];
+  for (int k0 = slice; k0 < chunks; k0 += 512) {
+    U4H a[8], b[8];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int u = 0; u < 8; ++u) {
       const int k = k0 + 64 * u;
       const int kk = k < chunks ? k : k0;             // a repeated chunk changes nothing
       a[u].u = p4[(kk * 2) * 16];
       b[u].u = p4[(kk * 2 + 1) * 16];
     }
 #pragma unroll
-    for (int u = 0; u < 4; ++u)
+    for (int u = 0; u < 8; ++u)
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         mn[i] = __builtin_elementwise_min(mn[i], a[u].h[i]);

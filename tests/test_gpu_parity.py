@@ -156,6 +156,21 @@ def test_gqa_ratios_batch_and_layers(Hkv, Hq):
             P.assert_out_close(out[b], ref, f"gqa {Hkv}/{Hq} l{layer} b{b}")
 
 
+def test_one_long_head_many_split_parts():
+    """One KV head with a long sequence: the split count goes far above what the
+    one-round merge takes, so the general merge kernel is the one checked here."""
+    base = synth.reduced(synth.WORKLOADS["c4_long"], 496)
+    w = dataclasses.replace(base, Hkv=1, Hq=7, T_tail=40)
+    print("[case] one long head", flush=True)
+    run = P.GpuRun(w, DEV)
+    q = synth.query(w, 0)
+    Kt, Vt, Ktd, Vtd = _tails(w, 0, 64)
+    tl = torch.tensor([40], dtype=torch.int32, device=DEV)
+    out = run.attention(0, torch.from_numpy(q).to(DEV), Ktd, Vtd, 64, tl).cpu().numpy()
+    ref = P.oracle_attention(run, 0, 0, q[0], Kt[0][:, :40], Vt[0][:, :40])
+    P.assert_out_close(out[0], ref, "one long head")
+
+
 def test_no_quantized_tokens_is_plain_attention():
     w = dataclasses.replace(synth.WORKLOADS["c2_layer"], frames=0, n_salient=0, B=2)
     print("[case] Tq=0", flush=True)

@@ -153,8 +153,9 @@ vidkv_status vidkv_quantize_values(const vidkv_params *params, const void *V_dev
  * that it runs beside the key passes.  The side stream starts after
  * everything already enqueued on `hip_stream` and is joined back before the
  * value coding pass: to the caller all work is ordered on `hip_stream` as
- * usual.  This is the one entry point that creates HIP objects (that stream
- * and two events); it has not been exercised under stream capture.
+ * usual.  The stream and its two events are created at the first call that
+ * needs them (make that call once outside a stream capture); fork and join
+ * are plain event record / wait pairs and are captured with the rest.
  * Arguments as for the two separate calls;
  *   workspace_dev : >= vidkv_workspace_bytes(params, 3) bytes                 */
 vidkv_status vidkv_quantize_kv(const vidkv_params *params, const void *K_dev,
@@ -180,7 +181,12 @@ vidkv_status vidkv_quantize_kv(const vidkv_params *params, const void *K_dev,
  *   workspace_dev   : >= vidkv_workspace_bytes(params, 2) bytes (the size
  *                     depends on t_capacity, not on t_quant)
  * With Tq == 0 this is plain attention over the residual tokens; a sequence
- * with no token at all gets zeros.                                            */
+ * with no token at all gets zeros.
+ * A large residual block (1024 or more 32-token blocks over all sequences and
+ * KV heads, at most 8 counted per head) is read by a kernel that is forked
+ * onto the library's side stream (see vidkv_quantize_kv) and joined before
+ * the split partials are merged; to the caller all work stays ordered on
+ * `hip_stream`.                                                               */
 vidkv_status vidkv_decode_attention(const vidkv_params *params, int32_t layer,
                                     const void *q_dev, const void *packed_K_dev,
                                     const void *packed_V_dev, const void *K_tail_dev,

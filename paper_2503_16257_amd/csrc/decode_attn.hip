@@ -442,10 +442,22 @@ int attn_num_splits(const Geom& g) {
   return (int)n;
 }
 
+// A large block of residual tokens is worth a stream of its own: its kernel is short of
+// memory parallelism, not of arithmetic, and runs well beside the MFMA kernel.
+bool attn_tail_beside(const Geom& g, int cap) {
+  if (cap <= 0 || g.ng == 0 || !attn_mfma_supported(g.n_a)) return false;
+  const int iters = (cap + 31) / 32;
+  const long long wgs = (long long)(iters < ATTN_TAIL_SPLITS ? iters : ATTN_TAIL_SPLITS) * g.B * g.H;
+  return wgs >= 1024;
+}
+
+// side / fork / join: when side is not null (and there are residual tokens for the MFMA
+// path) the residual-token kernel is forked onto that stream and joined before the merge.
 hipError_t launch_decode_attention(const Geom& g, int layer, float scale, const void* q,
                                    const uint8_t* pk, const uint8_t* pv, const void* ktail,
                                    const void* vtail, int cap, const int32_t* tail_len, void* out,
-                                   void* ws, unsigned stages, hipStream_t st) {
+                                   void* ws, unsigned stages, hipStream_t st, hipStream_t side,
+                                   hipEvent_t fork, hipEvent_t join) {
   AttnArgs a;
   a.q = reinterpret_cast<const _Float16*>(q);
   a.kperm = pk + g.k_perm;
@@ -478,9 +490,17 @@ hipError_t launch_decode_attention(const Geom& g, int layer, float scale, const 
     if (mfma) {
       const int npairs = (g.ng + 1) / 2;
       a.gps = (npairs + a.nsplit - 1) / a.nsplit;          // pairs per split
-      launch_attn_mfma(a, dim3(a.nsplit, g.H, g.B), st);
-      if (has_tail) {
-        hipLaunchKernelGGL(attn_tail_kernel, dim3(ntail, g.H, g.B), dim3(256), 0, st, a);
+      if (has_tail && side) {
+        if (hipEventRecord(fork, st) != hipSuccess) return hipErrorUnknown;
+        if (hipStreamWaitEvent(side, fork, 0) != hipSuccess) return hipErrorUnknown;
+        hipLaunchKernelGGL(attn_tail_kernel, dim3(ntail, g.H, g.B), dim3(256), 0, side, a);
+        if (hipEventRecord(join, side) != hipSuccess) return hipErrorUnknown;
+        launch_attn_mfma(a, dim3(a.nsplit, g.H, g.B), st);
+        if (hipStreamWaitEvent(st, join, 0) != hipSuccess) return hipErrorUnknown;
+      } else {
+        launch_attn_mfma(a, dim3(a.nsplit, g.H, g.B), st);
+        if (has_tail)
+          hipLaunchKernelGGL(attn_tail_kernel, dim3(ntail, g.H, g.B), dim3(256), 0, st, a);
       }
     } else {
       a.gps = a.nsplit ? (g.ng + a.nsplit - 1) / a.nsplit : 0;

@@ -14,7 +14,9 @@ size_t values_ws_bytes(const Geom& g);
 hipError_t launch_decode_attention(const Geom& g, int layer, float scale, const void* q,
                                    const uint8_t* pk, const uint8_t* pv, const void* ktail,
                                    const void* vtail, int cap, const int32_t* tail_len, void* out,
-                                   void* ws, unsigned stages, hipStream_t st);
+                                   void* ws, unsigned stages, hipStream_t st, hipStream_t side,
+                                   hipEvent_t fork, hipEvent_t join);
+bool attn_tail_beside(const Geom& g, int cap);
 int attn_num_splits(const Geom& g);
 void launch_k_encode(const Geom& g, const EncodeSpan& sp, const void* K, uint8_t* packed,
                      bool use_fft, hipStream_t st);
@@ -214,10 +216,20 @@ vidkv_status vidkv_decode_attention_stages(const vidkv_params* p, int32_t layer,
       !aligned(K_tail, 16) || !aligned(V_tail, 16) || !aligned(ws, 256) || !aligned(tail_len, 4))
     return VIDKV_EINVAL;
   if (ws_bytes < ws_attn(g)) return VIDKV_ENOSPACE;
-  const hipError_t e = launch_decode_attention(
-      g, layer, p->softmax_scale, q, static_cast<const uint8_t*>(packed_K),
-      static_cast<const uint8_t*>(packed_V), K_tail, V_tail, tail_capacity, tail_len, out, ws,
-      stages, static_cast<hipStream_t>(stream));
+  const uint8_t* pk = static_cast<const uint8_t*>(packed_K);
+  const uint8_t* pv = static_cast<const uint8_t*>(packed_V);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (K_tail && V_tail && tail_len && (stages & 1u) && attn_tail_beside(g, tail_capacity)) {
+    std::lock_guard<std::mutex> lock(g_side_mutex);
+    SideStream* s = side_stream_locked();
+    if (!s) return VIDKV_EHIP;
+    return launch_decode_attention(g, layer, p->softmax_scale, q, pk, pv, K_tail, V_tail,
+                                   tail_capacity, tail_len, out, ws, stages, st, s->stream,
+                                   s->fork, s->join) == hipSuccess ? VIDKV_OK : VIDKV_EHIP;
+  }
+  const hipError_t e = launch_decode_attention(g, layer, p->softmax_scale, q, pk, pv, K_tail, V_tail,
+                                               tail_capacity, tail_len, out, ws, stages, st,
+                                               nullptr, nullptr, nullptr);
   return e == hipSuccess ? VIDKV_OK : VIDKV_EHIP;
 }
 

@@ -427,6 +427,35 @@ __global__ __launch_bounds__(1024) void attn_merge_small_kernel(const float* __r
   }
 }
 
+// At most 16 parts (large batches): one thread per channel holds every part, no LDS.
+__global__ __launch_bounds__(128) void attn_merge_tiny_kernel(const float* __restrict__ part,
+                                                              int nparts, int B, int Hq,
+                                                              _Float16* __restrict__ out) {
+  const int h = blockIdx.x, b = blockIdx.y, c = threadIdx.x;
+  float mi[16], oi[16], li[16];
+#pragma unroll
+  for (int u = 0; u < 16; ++u) {
+    const bool ok = u < nparts;
+    const float* p = part + (((long long)(ok ? u : 0) * B + b) * Hq + h) * PART_STRIDE;
+    mi[u] = ok ? p[D] : -INFINITY;
+    oi[u] = ok ? p[c] : 0.0f;
+    li[u] = ok ? p[D + 1] : 0.0f;
+  }
+  float M = mi[0];
+#pragma unroll
+  for (int u = 1; u < 16; ++u) M = fmaxf(M, mi[u]);
+  float o = 0.0f, l = 0.0f;
+#pragma unroll
+  for (int u = 0; u < 16; ++u) {
+    const float w = mi[u] == -INFINITY ? 0.0f : exp2f(mi[u] - M);
+    if (w != 0.0f) {                       // an empty part's sums are never looked at
+      o += w * oi[u];
+      l += w * li[u];
+    }
+  }
+  out[((long long)b * Hq + h) * D + c] = (_Float16)(l > 0.0f ? o / l : 0.0f);
+}
+
 // Number of split-T workgroups per (sequence, KV head).
 int attn_num_splits(const Geom& g) {
   if (g.ng == 0) return 0;
@@ -510,7 +539,7 @@ hipError_t launch_decode_attention(const Geom& g, int layer, float scale, const 
   if (stages & 2u) {
     _Float16* o16 = reinterpret_cast<_Float16*>(out);
     if (nparts <= 16)
-      hipLaunchKernelGGL(attn_merge_small_kernel<2>, dim3(g.Hq, g.B), dim3(1024), 0, st, a.part,
+      hipLaunchKernelGGL(attn_merge_tiny_kernel, dim3(g.Hq, g.B), dim3(128), 0, st, a.part,
                          nparts, g.B, g.Hq, o16);
     else if (nparts <= 136)
       hipLaunchKernelGGL(attn_merge_small_kernel<17>, dim3(g.Hq, g.B), dim3(1024), 0, st, a.part,

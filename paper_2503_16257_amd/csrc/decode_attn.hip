@@ -463,7 +463,11 @@ int attn_num_splits(const Geom& g) {
   const bool mfma = attn_mfma_supported(g.n_a);
   // MFMA kernel: 4 waves per workgroup, each wave walks pairs of groups; aim at
   // 512 workgroups on the chip and at least 2 pairs per wave.
-  const long long target = mfma ? 512 : 1024;
+  // (768 without protected tokens and n_a <= 32: those variants fit 3 workgroups per CU -
+  // when that still leaves a workgroup 16 pairs or more)
+  const long long npairs = (g.ng + 1) / 2;
+  long long target = mfma ? 512 : 1024;
+  if (mfma && g.n_s == 0 && g.n_a <= 32 && npairs * bh >= 768 * 16) target = 768;
   long long n = (target + bh - 1) / bh;
   const long long units = mfma ? ((g.ng + 1) / 2 + 7) / 8 : g.ng;
   if (n > units) n = units;

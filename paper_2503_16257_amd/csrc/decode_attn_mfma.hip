@@ -50,7 +50,7 @@ __device__ __forceinline__ float swap_max16(float v) {
 // in the latter case slot = token and code * s + z = (z + s/2) + sigma * s/2, sigma = +-1,
 // so the same sign-type operand serves, without the inverse DFT and with a constant term.
 template <int NA8, int SAL, bool FFT>
-__global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a) {
+__global__ __launch_bounds__(256, (SAL == 0 && NA8 <= 4) ? 3 : 2) void attn_mfma_kernel(AttnArgs a) {
   constexpr int NA = 8 * NA8, NN = D - NA;
   constexpr int NB = NN / 8;                 // normal 8-channel blocks
   constexpr int U = (NB + 3) / 4;            // K-steps over normal channels
@@ -69,7 +69,8 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a) {
   const long long hd = ((long long)a.layer * a.B + b) * a.H + kvh;
   const f4 zero = f4{0.f, 0.f, 0.f, 0.f};
 
-  __shared__ u32x4 kl4[4][2][KCH_MAX];       // per wave: key records of the two groups
+  constexpr bool KDMA = (SAL == 0);          // key records by direct loads into LDS (see prefetch)
+  __shared__ u32x4 kl4[KDMA ? 2 : 1][4][2][KCH_MAX];   // per wave: key records of the two groups
   __shared__ float pl[4][32][16];            // per wave: probabilities [token][column]
   __shared__ float al16[4][16];              // per wave: rescale factors per column
   __shared__ float ow[4][8][D];              // per wave partial outputs
@@ -147,16 +148,34 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a) {
   const uint8_t* krec_base = a.krec + hd * a.ngc * (long long)KREC;
   const uint8_t* vrec_base = a.vrec + hd * a.ngc * (long long)VREC;
 
-  // prefetch registers: key record chunks and value words of both groups, value
-  // scales of the group whose rows this lane owns in the PV tile (parity kb >> 1)
+  // Prefetch, one pair ahead.  Without protected tokens the key records go from memory
+  // straight into the other LDS buffer (lane l of a wave-wide global_load_lds_dwordx4 lands
+  // at M0 + 16 l, i.e. the record keeps its byte order): 16 registers fewer, which is what
+  // lets that variant run 3 waves per SIMD.  The compiler is not told about these LDS writes,
+  // so the wait that precedes the first read of a buffer is written out below - a wait for
+  // every outstanding load, which is why the variants with protected rows (whose row loads
+  // are issued late and needed late) keep the key records in registers instead.  The value
+  // words of both groups and the value scales of the group whose rows this lane owns in the
+  // PV tile (parity kb >> 1) go to registers.
+  const uint32_t kl_lds = (uint32_t)reinterpret_cast<uintptr_t>(&kl4[0][0][0][0]);
+  auto dma16 = [&](const u32x4* g, uint32_t lds_byte) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off nt"
+                 :: "s"(lds_byte), "v"(g) : "memory");
+  };
   u32x4 kpre[2][2], vwpre[2], vspre;
-  auto prefetch = [&](int p) {
+  auto prefetch = [&](int p, int buf) {
 #pragma unroll
     for (int grp = 0; grp < 2; ++grp) {
       const int g = min(2 * p + grp, a.ng - 1);
       const u32x4* ks = reinterpret_cast<const u32x4*>(krec_base + (long long)g * KREC);
-      kpre[grp][0] = __builtin_nontemporal_load(ks + (lane < KCH ? lane : 0));
-      kpre[grp][1] = __builtin_nontemporal_load(ks + (lane + 64 < KCH ? lane + 64 : 0));
+      if (KDMA) {
+        const uint32_t la = kl_lds + (uint32_t)((((buf * 4 + wave) * 2 + grp) * KCH_MAX) * 16);
+        dma16(ks + lane, la);
+        if (KCH > 64 && lane + 64 < KCH) dma16(ks + lane + 64, la + 1024u);
+      } else {
+        kpre[grp][0] = __builtin_nontemporal_load(ks + lane);
+        kpre[grp][1] = __builtin_nontemporal_load(ks + (lane + 64 < KCH ? lane + 64 : 0));
+      }
       const u32x4* vs = reinterpret_cast<const u32x4*>(vrec_base + (long long)g * VREC);
       vwpre[grp] = __builtin_nontemporal_load(vs + lane);
     }
@@ -196,7 +215,8 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a) {
   int sal_pg = -1;
   float sal_s0 = 0.f, sal_s1 = 0.f, sal_z0 = 0.f, sal_z1 = 0.f;
   int p = p_begin + wave;
-  if (p < p_end) prefetch(p);
+  int buf = 0;
+  if (p < p_end) prefetch(p, 0);
   if ((SAL != 0)) {
     load_masks(p, sm0c, sm1c, rkc);
     load_masks(p + 4, sm0n, sm1n, rkn);
@@ -208,14 +228,17 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a) {
     // ---- commit the prefetched data, start the next prefetch
     u32x4 vw[2];
     Op sv;
+    if (KDMA) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this pair's key records are in kl4[buf]
 #pragma unroll
     for (int grp = 0; grp < 2; ++grp) {
-      if (lane < KCH) kl4[wave][grp][lane] = kpre[grp][0];
-      if (lane + 64 < KCH) kl4[wave][grp][lane + 64] = kpre[grp][1];
+      if (!KDMA) {
+        kl4[0][wave][grp][lane] = kpre[grp][0];
+        if (lane + 64 < KCH) kl4[0][wave][grp][lane + 64] = kpre[grp][1];
+      }
       vw[grp] = vwpre[grp];
     }
     sv.q = vspre;
-    if (p + 4 < p_end) prefetch(p + 4);
+    if (p + 4 < p_end) prefetch(p + 4, buf ^ 1);
     uint32_t sm0f = 0, sm1f = 0, rkf = 0;        // masks of the pair after the next one
     if ((SAL != 0)) {
       if (sm0n | sm1n) issue_rows(sm0n, sm1n, rkn, rownext);
@@ -230,7 +253,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a) {
       f4 accCn[2] = {zero, zero};
 #pragma unroll
       for (int grp = 0; grp < 2; ++grp) {
-        const uint8_t* rec = reinterpret_cast<const uint8_t*>(&kl4[wave][grp][0]);
+        const uint8_t* rec = reinterpret_cast<const uint8_t*>(&kl4[buf][wave][grp][0]);
 #pragma unroll
         for (int u = 0; u < U; ++u) {
           const int blk = min(4 * u + kb, NB - 1);
@@ -295,7 +318,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a) {
       f4 accC = zero;
 #pragma unroll
       for (int grp = 0; grp < 2; ++grp) {
-        const uint8_t* rec = reinterpret_cast<const uint8_t*>(&kl4[wave][grp][0]);
+        const uint8_t* rec = reinterpret_cast<const uint8_t*>(&kl4[buf][wave][grp][0]);
 #pragma unroll
         for (int ua = 0; ua < UA; ++ua) {
           const int quad = min(4 * ua + kb, NQ - 1);
@@ -504,6 +527,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a) {
 #pragma unroll
       for (int j = 0; j < NROW; ++j) rowcur[j] = rownext[j];
     }
+    if (KDMA) buf ^= 1;
   }
 
   // ---------------- per-wave reduction

@@ -157,6 +157,8 @@ __global__ __launch_bounds__(256, (SAL == 0 && NA8 <= 4) ? 3 : 2) void attn_mfma
   // are issued late and needed late) keep the key records in registers instead.  The value
   // words of both groups and the value scales of the group whose rows this lane owns in the
   // PV tile (parity kb >> 1) go to registers.
+  // (M0, the LDS base of the transfer, is written inside the asm statement; it is a reserved
+  // register that the compiler sets itself right before each of its own uses.)
   const uint32_t kl_lds = (uint32_t)reinterpret_cast<uintptr_t>(&kl4[0][0][0][0]);
   auto dma16 = [&](const u32x4* g, uint32_t lds_byte) {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off nt"

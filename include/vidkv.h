@@ -150,7 +150,8 @@ vidkv_status vidkv_quantize_values(const vidkv_params *params, const void *V_dev
  * The protected-token selection - a chain of short dependent launches - is
  * enqueued on a side stream owned by the library (one per device, default
  * priority, created at the first call and kept until the process ends) so
- * that it runs beside the key passes.  The side stream starts after
+ * that it runs beside the key passes (only when the key tensor is 32 MiB or
+ * more; smaller inputs run in line).  The side stream starts after
  * everything already enqueued on `hip_stream` and is joined back before the
  * value coding pass: to the caller all work is ordered on `hip_stream` as
  * usual.  The stream and its two events are created at the first call that

@@ -177,7 +177,10 @@ vidkv_status vidkv_quantize_kv(const vidkv_params* p, const void* K, const void*
   void* ws_v = static_cast<uint8_t*>(ws) + ws_keys(g);
   const float* sc = g.n_s > 0 ? saliency : nullptr;
   const int32_t* ix = g.n_s > 0 ? salient_idx : nullptr;
-  if (g.n_s > 0 && g.T > 0) {
+  // The fork and join cost about as much as three short launches, so the side stream pays
+  // only when the key passes are long enough to hide the selection chain behind them.
+  const bool fork = (size_t)g.nheads * g.T * D * 2 >= ((size_t)32 << 20);
+  if (g.n_s > 0 && g.T > 0 && fork) {
     // the chain of short selection launches runs beside the bandwidth-bound key passes
     std::lock_guard<std::mutex> lock(g_side_mutex);
     SideStream* s = side_stream_locked();

@@ -121,7 +121,7 @@ def test_large_residual_block_forked_inside_the_capture():
 def test_quantizer_with_its_side_stream_captured_and_replayed():
     """vidkv_quantize_kv forks the protected-token selection onto the library's side stream;
     captured, every replay must write the same bytes as the eager call."""
-    w = synth.reduced(synth.WORKLOADS["c4_long"], 16)
+    w = synth.reduced(synth.WORKLOADS["c4_long"], 176)       # 35 MB of keys: large enough to fork
     print("[case] graph-quantize", flush=True)
     run = P.GpuRun(w, DEV)                                   # eager reference buffers run.pk, run.pv
     sal = torch.from_numpy(synth.saliency(w)).to(DEV)

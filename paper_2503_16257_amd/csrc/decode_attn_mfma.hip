@@ -76,71 +76,10 @@ __global__ __launch_bounds__(256, (SAL == 0 && NA8 <= 4) ? 3 : 2) void attn_mfma
   __shared__ float ow[4][8][D];              // per wave partial outputs
   __shared__ float mw[4][8], lw[4][8];
   __shared__ _Float16 qs[8][D];
-  __shared__ uint8_t perm_s[D];
+  __shared__ __align__(16) uint8_t perm_s[D];
 
-  // ---------------- constant operands (q and the channel permutation via LDS)
-  {
-    const uint32_t* qsrc = reinterpret_cast<const uint32_t*>(a.q + ((long long)b * a.Hq + kvh * R) * D);
-    for (int i = tid; i < R * (D / 2); i += 256) reinterpret_cast<uint32_t*>(&qs[0][0])[i] = qsrc[i];
-    if (tid < D / 4)
-      reinterpret_cast<uint32_t*>(perm_s)[tid] = reinterpret_cast<const uint32_t*>(a.kperm + hd * D)[tid];
-  }
-  __syncthreads();
-  const bool hv = hcol < R;
-  const _Float16* qrow = &qs[hv ? hcol : 0][0];
-  Op Bn[U > 0 ? U : 1];                      // normal channels: -q/16 (FFT) or -q/2 at channels 8 (4u+kb) + e
-#pragma unroll
-  for (int u = 0; u < U; ++u) {
-    const int blk = 4 * u + kb;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      float v = 0.0f;
-      if (hv && blk < NB) v = -(float)qrow[perm_s[NA + 8 * blk + e]] * (FFT ? 0.0625f : 0.5f);
-      Bn[u].v[e] = (_Float16)v;
-    }
-  }
-  Op Ba[2][UA > 0 ? UA : 1];                 // anomalous: (-q, -q) per channel, only in my parity
-#pragma unroll
-  for (int ua = 0; ua < UA; ++ua) {
-    const int quad = 4 * ua + kb;
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      float v = 0.0f;
-      if (hv && quad < NQ) v = -(float)qrow[perm_s[4 * quad + r]];
-      const uint32_t pr = h2_bits(h2{(_Float16)v, (_Float16)v});
-      Ba[0][ua].u[r] = par ? 0u : pr;
-      Ba[1][ua].u[r] = par ? pr : 0u;
-    }
-  }
-  // 16 * (inverse real DFT matrix): row t, k-slot (kb, i): i < 4 -> Re X[4kb+i],
-  // i >= 4 -> Im X[4kb+i-4] (Re X[16] when that index is 0)
-  Op Wh[2], Wl[2];
-#pragma unroll
-  for (int mt = 0; mt < 2; ++mt) {
-    const int t = 16 * mt + x16;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int k = 4 * kb + (i & 3);
-      float w;
-      if (i < 4) w = (k == 0) ? 0.5f : kCosT[(k * t) & 31];
-      else       w = (k == 0) ? ((t & 1) ? -0.5f : 0.5f) : -kCosT[(k * t + 24) & 31];
-      const _Float16 hi = (_Float16)w;
-      Wh[mt].v[i] = hi;
-      Wl[mt].v[i] = (_Float16)(w - (float)hi);
-    }
-  }
-
-  // ---------------- running state
-  // o[m][i]: row 4kb+i = (parity, head) column of the score tile, channel 16 m + x16;
-  // holds 2 * sum p * code * s of the quantized tokens (halved at the end).
-  f4 o[8];
-#pragma unroll
-  for (int m = 0; m < 8; ++m) o[m] = zero;
-  float osal[8][2];                          // protected rows: head h, channels 2 lane, 2 lane + 1
-#pragma unroll
-  for (int h = 0; h < 8; ++h) { osal[h][0] = 0.f; osal[h][1] = 0.f; }
-  float m_run = -INFINITY, l_run = 0.0f;     // of my column (shared by both parities of a head)
-
+  // ---------------- first prefetch: issued before anything else so that its latency runs
+  // under the operand set-up below
   const int npairs = (a.ng + 1) >> 1;
   const int p_begin = split * a.gps;
   const int p_end = min(npairs, p_begin + a.gps);
@@ -218,12 +157,98 @@ __global__ __launch_bounds__(256, (SAL == 0 && NA8 <= 4) ? 3 : 2) void attn_mfma
   float sal_s0 = 0.f, sal_s1 = 0.f, sal_z0 = 0.f, sal_z1 = 0.f;
   int p = p_begin + wave;
   int buf = 0;
-  if (p < p_end) prefetch(p, 0);
-  if ((SAL != 0)) {
-    load_masks(p, sm0c, sm1c, rkc);
-    load_masks(p + 4, sm0n, sm1n, rkn);
-    if (sm0c | sm1c) issue_rows(sm0c, sm1c, rkc, rowcur);
+  // every load of the set-up is issued before the first wait: q and the permutation (to
+  // registers, then LDS), the first pair's records, the masks of the first two pairs
+  {
+    const uint32_t* qsrc = reinterpret_cast<const uint32_t*>(a.q + ((long long)b * a.Hq + kvh * R) * D);
+    const int nq = R * (D / 2);                // at most 512 dwords
+    const uint32_t q0 = tid < nq ? qsrc[tid] : 0u;
+    const uint32_t q1 = tid + 256 < nq ? qsrc[tid + 256] : 0u;
+    const uint32_t pw = tid < D / 4 ? reinterpret_cast<const uint32_t*>(a.kperm + hd * D)[tid] : 0u;
+    if (p < p_end) prefetch(p, 0);
+    if ((SAL != 0)) {
+      load_masks(p, sm0c, sm1c, rkc);
+      load_masks(p + 4, sm0n, sm1n, rkn);
+    }
+    // ---------------- constant operands (q and the channel permutation via LDS)
+    if (tid < nq) reinterpret_cast<uint32_t*>(&qs[0][0])[tid] = q0;
+    if (tid + 256 < nq) reinterpret_cast<uint32_t*>(&qs[0][0])[tid + 256] = q1;
+    if (tid < D / 4) reinterpret_cast<uint32_t*>(perm_s)[tid] = pw;
   }
+  __syncthreads();
+  if ((SAL != 0) && (sm0c | sm1c)) issue_rows(sm0c, sm1c, rkc, rowcur);
+  const bool hv = hcol < R;
+  const _Float16* qrow = &qs[hv ? hcol : 0][0];
+  // The permutation bytes of my channel blocks and quads come in one LDS read each, then
+  // every q element in one batch of independent reads (no branch around a read: absent
+  // blocks read a valid block and are zeroed afterwards).
+  Op Bn[U > 0 ? U : 1];                      // normal channels: -q/16 (FFT) or -q/2 at channels 8 (4u+kb) + e
+  Op Ba[2][UA > 0 ? UA : 1];                 // anomalous: (-q, -q) per channel, only in my parity
+  {
+    uint2 pb[U > 0 ? U : 1];
+    uint32_t pq[UA > 0 ? UA : 1];
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      pb[u] = *reinterpret_cast<const uint2*>(&perm_s[NA + 8 * min(4 * u + kb, NB - 1)]);
+#pragma unroll
+    for (int ua = 0; ua < UA; ++ua)
+      pq[ua] = *reinterpret_cast<const uint32_t*>(&perm_s[4 * min(4 * ua + kb, NQ - 1)]);
+    _Float16 qn[U > 0 ? U : 1][8], qa[UA > 0 ? UA : 1][4];
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) qn[u][e] = qrow[((e < 4 ? pb[u].x : pb[u].y) >> (8 * (e & 3))) & 0xFFu];
+#pragma unroll
+    for (int ua = 0; ua < UA; ++ua)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) qa[ua][r] = qrow[(pq[ua] >> (8 * r)) & 0xFFu];
+    const _Float16 cn = (_Float16)(FFT ? -0.0625f : -0.5f);
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const bool ok = hv && (4 * u + kb) < NB;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) Bn[u].v[e] = ok ? (_Float16)(qn[u][e] * cn) : (_Float16)0.0f;
+    }
+#pragma unroll
+    for (int ua = 0; ua < UA; ++ua) {
+      const bool ok = hv && (4 * ua + kb) < NQ;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const _Float16 v = ok ? (_Float16)(-qa[ua][r]) : (_Float16)0.0f;
+        const uint32_t pr = h2_bits(h2{v, v});
+        Ba[0][ua].u[r] = par ? 0u : pr;
+        Ba[1][ua].u[r] = par ? pr : 0u;
+      }
+    }
+  }
+  // 16 * (inverse real DFT matrix): row t, k-slot (kb, i): i < 4 -> Re X[4kb+i],
+  // i >= 4 -> Im X[4kb+i-4] (Re X[16] when that index is 0)
+  Op Wh[2], Wl[2];
+#pragma unroll
+  for (int mt = 0; mt < 2; ++mt) {
+    const int t = 16 * mt + x16;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int k = 4 * kb + (i & 3);
+      float w;
+      if (i < 4) w = (k == 0) ? 0.5f : kCosT[(k * t) & 31];
+      else       w = (k == 0) ? ((t & 1) ? -0.5f : 0.5f) : -kCosT[(k * t + 24) & 31];
+      const _Float16 hi = (_Float16)w;
+      Wh[mt].v[i] = hi;
+      Wl[mt].v[i] = (_Float16)(w - (float)hi);
+    }
+  }
+
+  // ---------------- running state
+  // o[m][i]: row 4kb+i = (parity, head) column of the score tile, channel 16 m + x16;
+  // holds 2 * sum p * code * s of the quantized tokens (halved at the end).
+  f4 o[8];
+#pragma unroll
+  for (int m = 0; m < 8; ++m) o[m] = zero;
+  float osal[8][2];                          // protected rows: head h, channels 2 lane, 2 lane + 1
+#pragma unroll
+  for (int h = 0; h < 8; ++h) { osal[h][0] = 0.f; osal[h][1] = 0.f; }
+  float m_run = -INFINITY, l_run = 0.0f;     // of my column (shared by both parities of a head)
 
   for (; p < p_end; p += 4) {
     const bool v1ok = (2 * p + 1) < a.ng;

@@ -78,8 +78,7 @@ __global__ __launch_bounds__(256, (SAL == 0 && NA8 <= 4) ? 3 : 2) void attn_mfma
   __shared__ _Float16 qs[8][D];
   __shared__ __align__(16) uint8_t perm_s[D];
 
-  // ---------------- first prefetch: issued before anything else so that its latency runs
-  // under the operand set-up below
+  // ---------------- prefetch machinery (the first request is placed in the set-up below)
   const int npairs = (a.ng + 1) >> 1;
   const int p_begin = split * a.gps;
   const int p_end = min(npairs, p_begin + a.gps);
@@ -157,15 +156,13 @@ __global__ __launch_bounds__(256, (SAL == 0 && NA8 <= 4) ? 3 : 2) void attn_mfma
   float sal_s0 = 0.f, sal_s1 = 0.f, sal_z0 = 0.f, sal_z1 = 0.f;
   int p = p_begin + wave;
   int buf = 0;
-  // every load of the set-up is issued before the first wait: q and the permutation (to
-  // registers, then LDS), the first pair's records, the masks of the first two pairs
+  // q and the permutation (to registers, then LDS) and the masks of the first two pairs
   {
     const uint32_t* qsrc = reinterpret_cast<const uint32_t*>(a.q + ((long long)b * a.Hq + kvh * R) * D);
     const int nq = R * (D / 2);                // at most 512 dwords
     const uint32_t q0 = tid < nq ? qsrc[tid] : 0u;
     const uint32_t q1 = tid + 256 < nq ? qsrc[tid + 256] : 0u;
     const uint32_t pw = tid < D / 4 ? reinterpret_cast<const uint32_t*>(a.kperm + hd * D)[tid] : 0u;
-    if (p < p_end) prefetch(p, 0);
     if ((SAL != 0)) {
       load_masks(p, sm0c, sm1c, rkc);
       load_masks(p + 4, sm0n, sm1n, rkn);
@@ -176,6 +173,10 @@ __global__ __launch_bounds__(256, (SAL == 0 && NA8 <= 4) ? 3 : 2) void attn_mfma
     if (tid < D / 4) reinterpret_cast<uint32_t*>(perm_s)[tid] = pw;
   }
   __syncthreads();
+  // The first pair's records are requested only now.  All workgroups start together, and
+  // their first requests are a burst of many MB; q, asked for behind that burst, would
+  // arrive after it.  This way q is in first and the burst runs under the operand set-up.
+  if (p < p_end) prefetch(p, 0);
   if ((SAL != 0) && (sm0c | sm1c)) issue_rows(sm0c, sm1c, rkc, rowcur);
   const bool hv = hcol < R;
   const _Float16* qrow = &qs[hv ? hcol : 0][0];

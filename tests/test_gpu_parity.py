@@ -173,6 +173,26 @@ def test_one_long_head_many_split_parts():
     P.assert_out_close(out[0], ref, "one long head")
 
 
+def test_large_residual_block_with_ragged_lengths():
+    """A batch whose residual block is large enough to be read on the library's side stream,
+    with lengths from 0 to the capacity: sampled sequences against the oracle."""
+    w = synth.reduced(synth.WORKLOADS["c5_serving"], 8, B=32)
+    print("[case] forked residual block, ragged", flush=True)
+    run = P.GpuRun(w, DEV)
+    cap = 256
+    q = synth.query(w, 0)
+    Kt, Vt, Ktd, Vtd = _tails(w, 0, cap)
+    rng = np.random.default_rng(5)
+    tl_np = rng.integers(0, cap + 1, size=w.B).astype(np.int32)
+    tl_np[0], tl_np[1], tl_np[2] = 0, cap, 1
+    tl = torch.from_numpy(tl_np).to(DEV)
+    out = run.attention(0, torch.from_numpy(q).to(DEV), Ktd, Vtd, cap, tl).cpu().numpy()
+    for b in (0, 1, 2, 17, 31):
+        n = int(tl_np[b])
+        ref = P.oracle_attention(run, 0, b, q[b], Kt[b][:, :n], Vt[b][:, :n])
+        P.assert_out_close(out[b], ref, f"forked residual block b{b} len {n}")
+
+
 def test_no_quantized_tokens_is_plain_attention():
     w = dataclasses.replace(synth.WORKLOADS["c2_layer"], frames=0, n_salient=0, B=2)
     print("[case] Tq=0", flush=True)

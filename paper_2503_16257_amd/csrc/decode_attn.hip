@@ -427,14 +427,15 @@ __global__ __launch_bounds__(1024) void attn_merge_small_kernel(const float* __r
   }
 }
 
-// At most 16 parts (large batches): one thread per channel holds every part, no LDS.
+// At most MAXP parts (large batches): one thread per channel holds every part, no LDS.
+template <int MAXP>
 __global__ __launch_bounds__(128) void attn_merge_tiny_kernel(const float* __restrict__ part,
                                                               int nparts, int B, int Hq,
                                                               _Float16* __restrict__ out) {
   const int h = blockIdx.x, b = blockIdx.y, c = threadIdx.x;
-  float mi[16], oi[16], li[16];
+  float mi[MAXP], oi[MAXP], li[MAXP];
 #pragma unroll
-  for (int u = 0; u < 16; ++u) {
+  for (int u = 0; u < MAXP; ++u) {
     const bool ok = u < nparts;
     const float* p = part + (((long long)(ok ? u : 0) * B + b) * Hq + h) * PART_STRIDE;
     mi[u] = ok ? p[D] : -INFINITY;
@@ -443,10 +444,10 @@ __global__ __launch_bounds__(128) void attn_merge_tiny_kernel(const float* __res
   }
   float M = mi[0];
 #pragma unroll
-  for (int u = 1; u < 16; ++u) M = fmaxf(M, mi[u]);
+  for (int u = 1; u < MAXP; ++u) M = fmaxf(M, mi[u]);
   float o = 0.0f, l = 0.0f;
 #pragma unroll
-  for (int u = 0; u < 16; ++u) {
+  for (int u = 0; u < MAXP; ++u) {
     const float w = mi[u] == -INFINITY ? 0.0f : exp2f(mi[u] - M);
     if (w != 0.0f) {                       // an empty part's sums are never looked at
       o += w * oi[u];
@@ -543,7 +544,10 @@ hipError_t launch_decode_attention(const Geom& g, int layer, float scale, const 
   if (stages & 2u) {
     _Float16* o16 = reinterpret_cast<_Float16*>(out);
     if (nparts <= 16)
-      hipLaunchKernelGGL(attn_merge_tiny_kernel, dim3(g.Hq, g.B), dim3(128), 0, st, a.part,
+      hipLaunchKernelGGL(attn_merge_tiny_kernel<16>, dim3(g.Hq, g.B), dim3(128), 0, st, a.part,
+                         nparts, g.B, g.Hq, o16);
+    else if (nparts <= 32)
+      hipLaunchKernelGGL(attn_merge_tiny_kernel<32>, dim3(g.Hq, g.B), dim3(128), 0, st, a.part,
                          nparts, g.B, g.Hq, o16);
     else if (nparts <= 136)
       hipLaunchKernelGGL(attn_merge_small_kernel<17>, dim3(g.Hq, g.B), dim3(1024), 0, st, a.part,

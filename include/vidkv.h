@@ -16,7 +16,11 @@
  *    `params` is HOST memory.  The caller owns every buffer; the library
  *    allocates no memory, keeps no pointer after a call returns and never
  *    synchronizes: all work is enqueued on `hip_stream` (a hipStream_t passed
- *    as void*, NULL = the default stream).
+ *    as void*, NULL = the default stream).  vidkv_quantize_kv and
+ *    vidkv_decode_attention may run part of a large call on a side stream
+ *    that the library owns, forked from and joined back into `hip_stream`
+ *    by events, so that to the caller everything stays ordered on
+ *    `hip_stream` (see those functions).
  *  - All arguments are checked on the host before anything is launched; a
  *    failed check returns a status and launches nothing.  A launch failure
  *    returns VIDKV_EHIP.  Nothing aborts or throws across this boundary.

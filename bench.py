@@ -38,6 +38,14 @@ MEASURED_TRAFFIC_BYTES = {
 }
 
 
+# The attention kernel is bound by vector-ALU issue, not by HBM: its second roofline is the
+# number of VALU instructions it executes (rocprofv3 --pmc SQ_INSTS_VALU, per launch, MFMA
+# instructions included; see profiles/c4_long_attention_valu.md) x 64 lanes against
+# one instruction per lane and cycle on 256 CUs x 4 SIMDs x 16 lanes at 2.4 GHz.
+MEASURED_VALU_INSTS = {"c4_long": {"attn_partial": 9.437e6}}
+VALU_PEAK_TLANEOPS = 256 * 4 * 16 * 2.4e9 / 1e12
+
+
 def algorithmic_bytes(w):
     """Bytes the method itself must move, per kernel, for workload w."""
     N = w.L * w.B * w.Hkv * w.T * 128                       # elements per tensor
@@ -315,6 +323,12 @@ def main():
                 "us": round(kt[name] * 1e6, 2)}
 
     roofs = [roof("k_range"), roof("k_encode"), roof("v_encode"), roof("attn_partial", w.L)]
+    vi = MEASURED_VALU_INSTS.get(w.name, {}).get("attn_partial")
+    if vi is not None and not args.no_fft and args.salient_bits == 16:
+        ach = vi * 64 / kt["attn_partial"] / 1e12
+        roofs[-1]["alu"] = {"bound": "alu", "achieved": round(ach, 2), "peak": round(VALU_PEAK_TLANEOPS, 2),
+                            "unit": "T VALU lane-ops/s", "frac": round(ach / VALU_PEAK_TLANEOPS, 4),
+                            "valu_instructions": round(vi)}
     dominant = max(roofs, key=lambda r: r["us"] * (w.L if r["kernel"] == "attn_partial" else 1))
     if "saliency" in kt:                       # outside the step, listed for its own roofline
         roofs.append(roof("saliency"))

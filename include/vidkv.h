@@ -200,6 +200,29 @@ vidkv_status vidkv_decode_attention(const vidkv_params *params, int32_t layer,
                                     void *workspace_dev, size_t workspace_bytes,
                                     void *hip_stream);
 
+/* vidkv_decode_attention for callers that cannot allocate device memory or
+ * carry a workspace: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments, checks and result as
+ * vidkv_decode_attention, without the workspace: the split partials go to a
+ * device array inside the library's image, VIDKV_NOALLOC_SCRATCH_BYTES large,
+ * which every GPU that runs the library holds until the process ends.  The
+ * call allocates nothing and creates no stream or event; all of its kernels,
+ * the one for a large residual block included, run in line on `hip_stream`.
+ * A shape whose partials (what vidkv_workspace_bytes(params, 2) reports) do
+ * not fit the array returns VIDKV_ENOSPACE and launches nothing.  The device
+ * address of the array is looked up at the first call on each device (make
+ * that call outside a stream capture).  All calls on one GPU share the one
+ * array: two such calls that may run at the same time - on different streams
+ * of that GPU, or from different host threads - race and give wrong results;
+ * calls ordered on one stream are fine.                                        */
+#define VIDKV_NOALLOC_SCRATCH_BYTES (16u << 20)
+vidkv_status vidkv_decode_attention_noalloc(const vidkv_params *params, int32_t layer,
+                                            const void *q_dev, const void *packed_K_dev,
+                                            const void *packed_V_dev, const void *K_tail_dev,
+                                            const void *V_tail_dev, int32_t tail_capacity,
+                                            const int32_t *tail_len_dev, void *out_dev,
+                                            void *hip_stream);
+
 /* Alg. 1, Decoding, the step taken when the residual buffers are full (R
  * tokens): the first n_flush residual tokens of every sequence of one layer
  * are coded and appended to the packed buffers as tokens t_quant ..

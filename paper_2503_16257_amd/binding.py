@@ -74,6 +74,8 @@ def lib() -> C.CDLL:
         L.vidkv_saliency_scores.restype = C.c_int
         L.vidkv_decode_attention.argtypes = [PP, i32, vp, vp, vp, vp, vp, i32, vp, vp, vp, sz, vp]
         L.vidkv_decode_attention.restype = C.c_int
+        L.vidkv_decode_attention_noalloc.argtypes = [PP, i32, vp, vp, vp, vp, vp, i32, vp, vp, vp]
+        L.vidkv_decode_attention_noalloc.restype = C.c_int
         u32 = C.c_uint32
         L.vidkv_quantize_keys_stages.argtypes = [PP, vp, vp, sz, vp, sz, u32, vp]
         L.vidkv_quantize_keys_stages.restype = C.c_int
@@ -192,6 +194,20 @@ def decode_attention(p: VidkvParams, layer: int, q, packed_K, packed_V, out, wor
     else:
         _check(lib().vidkv_decode_attention_stages(*a, stages, _stream(stream)),
                "vidkv_decode_attention_stages")
+
+
+NOALLOC_SCRATCH_BYTES = 16 << 20     # VIDKV_NOALLOC_SCRATCH_BYTES of include/vidkv.h
+
+
+def decode_attention_noalloc(p: VidkvParams, layer: int, q, packed_K, packed_V, out, K_tail=None,
+                             V_tail=None, tail_capacity: int = 0, tail_len=None, stream=None) -> None:
+    """vidkv_decode_attention_noalloc: the decode step without a workspace argument."""
+    import torch
+    _check(lib().vidkv_decode_attention_noalloc(
+        C.byref(p), layer, _ptr(q, torch.float16, "q"), _ptr(packed_K, torch.uint8, "packed_K"),
+        _ptr(packed_V, torch.uint8, "packed_V"), _ptr(K_tail, torch.float16, "K_tail"),
+        _ptr(V_tail, torch.float16, "V_tail"), tail_capacity, _ptr(tail_len, torch.int32, "tail_len"),
+        _ptr(out, torch.float16, "out"), _stream(stream)), "vidkv_decode_attention_noalloc")
 
 
 def quantize_kv(p: VidkvParams, K, V, packed_K, packed_V, workspace, saliency=None,

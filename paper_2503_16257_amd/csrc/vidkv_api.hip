@@ -200,6 +200,25 @@ vidkv_status vidkv_quantize_kv(const vidkv_params* p, const void* K, const void*
              ? VIDKV_OK : VIDKV_EHIP;
 }
 
+// Argument checks of a decode step, shared by the entry points below.
+static vidkv_status check_decode(const vidkv_params* p, Geom* g, int32_t layer, const void* q,
+                                 const void* packed_K, const void* packed_V, const void* K_tail,
+                                 const void* V_tail, int32_t tail_capacity,
+                                 const int32_t* tail_len, const void* out) {
+  if (!p || !q || !out) return VIDKV_EINVAL;
+  if (!make_geom(p, g)) return VIDKV_ESHAPE;
+  if (layer < 0 || layer >= g->L) return VIDKV_EINVAL;
+  if (g->T > 0 && (!packed_K || !packed_V)) return VIDKV_EINVAL;
+  if (tail_capacity < 0) return VIDKV_EINVAL;
+  if (tail_capacity > 0 && tail_len && (!K_tail || !V_tail)) return VIDKV_EINVAL;
+  if (g->B > 65535 || g->H > 65535) return VIDKV_ESHAPE;
+  if (!(p->softmax_scale > 0.0f) || !(p->softmax_scale < 1e30f)) return VIDKV_EINVAL;
+  if (!aligned(q, 16) || !aligned(out, 16) || !aligned(packed_K, 256) || !aligned(packed_V, 256) ||
+      !aligned(K_tail, 16) || !aligned(V_tail, 16) || !aligned(tail_len, 4))
+    return VIDKV_EINVAL;
+  return VIDKV_OK;
+}
+
 vidkv_status vidkv_decode_attention_stages(const vidkv_params* p, int32_t layer, const void* q,
                                            const void* packed_K, const void* packed_V,
                                            const void* K_tail, const void* V_tail,
@@ -207,17 +226,11 @@ vidkv_status vidkv_decode_attention_stages(const vidkv_params* p, int32_t layer,
                                            void* out, void* ws, size_t ws_bytes, uint32_t stages,
                                            void* stream) {
   Geom g;
-  if (!p || !q || !out || !ws) return VIDKV_EINVAL;
-  if (!make_geom(p, &g)) return VIDKV_ESHAPE;
-  if (layer < 0 || layer >= g.L) return VIDKV_EINVAL;
-  if (g.T > 0 && (!packed_K || !packed_V)) return VIDKV_EINVAL;
-  if (tail_capacity < 0) return VIDKV_EINVAL;
-  if (tail_capacity > 0 && tail_len && (!K_tail || !V_tail)) return VIDKV_EINVAL;
-  if (g.B > 65535 || g.H > 65535) return VIDKV_ESHAPE;
-  if (!(p->softmax_scale > 0.0f) || !(p->softmax_scale < 1e30f)) return VIDKV_EINVAL;
-  if (!aligned(q, 16) || !aligned(out, 16) || !aligned(packed_K, 256) || !aligned(packed_V, 256) ||
-      !aligned(K_tail, 16) || !aligned(V_tail, 16) || !aligned(ws, 256) || !aligned(tail_len, 4))
-    return VIDKV_EINVAL;
+  if (!ws) return VIDKV_EINVAL;
+  const vidkv_status chk = check_decode(p, &g, layer, q, packed_K, packed_V, K_tail, V_tail,
+                                        tail_capacity, tail_len, out);
+  if (chk != VIDKV_OK) return chk;
+  if (!aligned(ws, 256)) return VIDKV_EINVAL;
   if (ws_bytes < ws_attn(g)) return VIDKV_ENOSPACE;
   const uint8_t* pk = static_cast<const uint8_t*>(packed_K);
   const uint8_t* pv = static_cast<const uint8_t*>(packed_V);
@@ -243,6 +256,58 @@ vidkv_status vidkv_decode_attention(const vidkv_params* p, int32_t layer, const 
                                     void* stream) {
   return vidkv_decode_attention_stages(p, layer, q, packed_K, packed_V, K_tail, V_tail,
                                        tail_capacity, tail_len, out, ws, ws_bytes, ~0u, stream);
+}
+
+}  // extern "C"
+
+// ---- decode step for callers that cannot allocate -------------------------------------------
+// The split partials of a decode step (o, m, l per split, sequence and query head) are the one
+// scratch buffer of the decode path.  Here they live in a device array that is part of the
+// library's image: every GPU that runs the library holds its own copy, at its own address,
+// until the process ends.  The array's name is only a handle on the host; its device address
+// is looked up once per device (with that device current) and kept.
+static __device__ __align__(256) unsigned char scratch[VIDKV_NOALLOC_SCRATCH_BYTES];
+
+namespace {
+void* g_scratch_ptr[MAX_DEVICES];
+std::mutex g_scratch_mutex;
+
+// device address of `scratch` on the current device; nullptr on failure
+void* scratch_on_current_device() {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return nullptr;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress((void**)&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return nullptr;
+    g_scratch_ptr[dev] = ptr;
+  }
+  return g_scratch_ptr[dev];
+}
+}  // namespace
+
+extern "C" {
+
+vidkv_status vidkv_decode_attention_noalloc(const vidkv_params* p, int32_t layer, const void* q,
+                                            const void* packed_K, const void* packed_V,
+                                            const void* K_tail, const void* V_tail,
+                                            int32_t tail_capacity, const int32_t* tail_len,
+                                            void* out, void* stream) {
+  Geom g;
+  const vidkv_status chk = check_decode(p, &g, layer, q, packed_K, packed_V, K_tail, V_tail,
+                                        tail_capacity, tail_len, out);
+  if (chk != VIDKV_OK) return chk;
+  if (ws_attn(g) > (size_t)VIDKV_NOALLOC_SCRATCH_BYTES) return VIDKV_ENOSPACE;
+  void* ws = scratch_on_current_device();
+  if (!ws) return VIDKV_EHIP;
+  // Everything runs in line on the caller's stream (the side stream of the other entry point
+  // would have to be created).  Nothing in the array has to start at zero: the merge reads
+  // only the parts that this call's kernels wrote before it.
+  const hipError_t e = launch_decode_attention(
+      g, layer, p->softmax_scale, q, static_cast<const uint8_t*>(packed_K),
+      static_cast<const uint8_t*>(packed_V), K_tail, V_tail, tail_capacity, tail_len, out, ws, ~0u,
+      static_cast<hipStream_t>(stream), nullptr, nullptr, nullptr);
+  return e == hipSuccess ? VIDKV_OK : VIDKV_EHIP;
 }
 
 vidkv_status vidkv_flush_residual(const vidkv_params* p, int32_t layer, const void* K_tail,

@@ -23,7 +23,8 @@ def test_library_exports_every_declared_symbol():
     names = _declared_functions()
     assert {"vidkv_quantize_keys", "vidkv_quantize_values", "vidkv_decode_attention",
             "vidkv_flush_residual", "vidkv_saliency_scores", "vidkv_quantize_kv", "vidkv_packed_keys_bytes", "vidkv_packed_values_bytes", "vidkv_workspace_bytes",
-            "vidkv_status_string", "vidkv_abi_version", "vidkv_calib_copy"} <= set(names)
+            "vidkv_status_string", "vidkv_abi_version", "vidkv_calib_copy",
+            "vidkv_decode_attention_noalloc"} <= set(names)
     L = C.CDLL(vk.LIB_PATH)
     for n in names:
         assert hasattr(L, n), n
@@ -119,6 +120,15 @@ def test_entry_points_refuse_bad_arguments_before_launch():
     assert call(a11=vk.workspace_bytes(p, 2) - 1) == vk.ENOSPACE
     noscale = vk.make_params(1, 1, 4, 28, 64, 16, 4, softmax_scale=0.0)
     assert call(a0=C.byref(noscale)) == vk.EINVAL
+    # the variant without a workspace: same checks, and a shape whose split partials exceed
+    # the library's own array is refused before anything touches the GPU
+    na = [pb, 0, A, A, A, None, None, 0, None, A, None]
+    assert L.vidkv_decode_attention_noalloc(pb, 1, *na[2:]) == vk.EINVAL
+    assert L.vidkv_decode_attention_noalloc(pb, 0, None, *na[3:]) == vk.EINVAL
+    assert L.vidkv_decode_attention_noalloc(pb, 0, A, A, A, None, None, -1, None, A, None) == vk.EINVAL
+    huge = vk.make_params(1, 4096, 4, 28, 64, 16, 0)
+    assert vk.workspace_bytes(huge, 2) > vk.NOALLOC_SCRATCH_BYTES
+    assert L.vidkv_decode_attention_noalloc(C.byref(huge), *na[1:]) == vk.ENOSPACE
     # flush_residual: needs room behind t_quant, whole groups, an existing channel selection
     roomy = vk.make_params(1, 1, 4, 28, 64, 16, 4, t_capacity=192)
     rb = C.byref(roomy)

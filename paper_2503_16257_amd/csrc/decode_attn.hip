@@ -11,6 +11,7 @@
 // fp16 residual tokens), the merge kernel and the launcher; the MFMA kernel
 // that handles the common channel counts is in decode_attn_mfma.hip.
 #include "decode_attn.h"
+#include <atomic>
 
 namespace vidkv {
 
@@ -457,18 +458,36 @@ __global__ __launch_bounds__(128) void attn_merge_tiny_kernel(const float* __res
   out[((long long)b * Hq + h) * D + c] = (_Float16)(l > 0.0f ? o / l : 0.0f);
 }
 
+// Compute units of the current device, asked once per device. A process with no usable
+// device (a size query on a build host) gets the MI355X figure, 256.
+static int device_cu_count() {
+  constexpr int MAXDEV = 64;
+  static std::atomic<int> cached[MAXDEV];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAXDEV) {
+    (void)hipGetLastError();
+    return 256;
+  }
+  int n = cached[dev].load(std::memory_order_relaxed);
+  if (n > 0) return n;
+  if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) {
+    (void)hipGetLastError();
+    n = 256;
+  }
+  cached[dev].store(n, std::memory_order_relaxed);
+  return n;
+}
+
 // Number of split-T workgroups per (sequence, KV head).
 int attn_num_splits(const Geom& g) {
   if (g.ng == 0) return 0;
   const long long bh = (long long)g.B * g.H;
   const bool mfma = attn_mfma_supported(g.n_a);
-  // MFMA kernel: 4 waves per workgroup, each wave walks pairs of groups; aim at
-  // 512 workgroups on the chip and at least 2 pairs per wave.
-  // (768 without protected tokens and n_a <= 32: those variants fit 3 workgroups per CU -
-  // when that still leaves a workgroup 16 pairs or more)
-  const long long npairs = (g.ng + 1) / 2;
-  long long target = mfma ? 512 : 1024;
-  if (mfma && g.n_s == 0 && g.n_a <= 32 && npairs * bh >= 768 * 16) target = 768;
+  // MFMA kernel: 4 waves per workgroup, each wave walks pairs of groups; two workgroups
+  // are resident per compute unit, so aim at one full round of them, and at no less than
+  // 8 pairs per workgroup. The scalar kernel runs four workgroups per compute unit.
+  const long long cus = device_cu_count();
+  const long long target = mfma ? 2 * cus : 4 * cus;
   long long n = (target + bh - 1) / bh;
   const long long units = mfma ? ((g.ng + 1) / 2 + 7) / 8 : g.ng;
   if (n > units) n = units;
@@ -482,7 +501,7 @@ bool attn_tail_beside(const Geom& g, int cap) {
   if (cap <= 0 || g.ng == 0 || !attn_mfma_supported(g.n_a)) return false;
   const int iters = (cap + 31) / 32;
   const long long wgs = (long long)(iters < ATTN_TAIL_SPLITS ? iters : ATTN_TAIL_SPLITS) * g.B * g.H;
-  return wgs >= 1024;
+  return wgs >= 4LL * device_cu_count();
 }
 
 // side / fork / join: when side is not null (and there are residual tokens for the MFMA

@@ -192,6 +192,7 @@ def main():
 
     vk.lib()                                  # fail loudly if the library is not built
     dev = "cuda:0"
+    side = vk.SideStream(dev)                 # the caller's side stream for the two calls that fork
     w = synth.WORKLOADS[args.workload]
     p = vk.make_params(w.L, w.B, w.Hkv, w.Hq, w.T, w.n_anom, w.n_salient,
                        gamma=float(np.float32(0.7)), use_fft=0 if args.no_fft else 1,
@@ -247,10 +248,10 @@ def main():
     def attn(i, stages=None):
         for l in range(w.L):
             vk.decode_attention(p, l, qs[l], pks[i % AROT], pvs[i % AROT], out, ws, K_tail=Kt,
-                                V_tail=Vt, tail_capacity=cap, tail_len=tl, stages=stages)
+                                V_tail=Vt, tail_capacity=cap, tail_len=tl, stages=stages, side=side)
 
     def q_kv(i):
-        vk.quantize_kv(p, Ks[i % NROT], Vs[i % NROT], pks[i % AROT], pvs[i % AROT], ws, saliency=sal)
+        vk.quantize_kv(p, Ks[i % NROT], Vs[i % NROT], pks[i % AROT], pvs[i % AROT], ws, saliency=sal, side=side)
 
     def step(i):
         q_kv(i)

@@ -16,11 +16,13 @@
  *    `params` is HOST memory.  The caller owns every buffer; the library
  *    allocates no memory, keeps no pointer after a call returns and never
  *    synchronizes: all work is enqueued on `hip_stream` (a hipStream_t passed
- *    as void*, NULL = the default stream).  vidkv_quantize_kv and
- *    vidkv_decode_attention may run part of a large call on a side stream
- *    that the library owns, forked from and joined back into `hip_stream`
- *    by events, so that to the caller everything stays ordered on
- *    `hip_stream` (see those functions).
+ *    as void*, NULL = the default stream), which must belong to the current
+ *    device (else VIDKV_EINVAL).  The library creates no stream and no event
+ *    and keeps no state between calls (the one exception is the device array
+ *    of vidkv_decode_attention_noalloc).  vidkv_quantize_kv and
+ *    vidkv_decode_attention can run part of a large call beside the rest on a
+ *    second stream that the caller hands in (vidkv_side_stream below); without
+ *    one, everything runs in line on `hip_stream`.
  *  - All arguments are checked on the host before anything is launched; a
  *    failed check returns a status and launches nothing.  A launch failure
  *    returns VIDKV_EHIP.  Nothing aborts or throws across this boundary.
@@ -37,8 +39,10 @@
  *    sequences x KV heads for a flush); larger shapes return VIDKV_ESHAPE
  *    and are to be split by the caller, e.g. one set of packed buffers (and
  *    one params with n_layers = 1) per layer.
- *  - The packed buffers are opaque to the caller; their byte sizes come from
- *    the vidkv_packed_*_bytes functions.  Packed buffers and workspaces must
+ *  - The byte sizes of the packed buffers come from the vidkv_packed_*_bytes
+ *    functions; their layout - every section, record, bit and byte order - is
+ *    written down in LAYOUT.md beside this header, and is part of the ABI
+ *    version.  Packed buffers and workspaces must
  *    be 256-byte aligned; fp16 tensors and the saliency scores 16-byte
  *    aligned; int32 arrays 4-byte aligned (else VIDKV_EINVAL).
  *  - A workspace is scratch: undefined contents on entry and exit, not to be
@@ -54,7 +58,7 @@
 extern "C" {
 #endif
 
-#define VIDKV_ABI_VERSION 2
+#define VIDKV_ABI_VERSION 3
 
 typedef enum {
   VIDKV_OK = 0,
@@ -99,6 +103,26 @@ typedef struct vidkv_params {
                             Variance, 2 number of Outliers |x| > 3 mean|x|;
                             1 and 2 are the paper's ablation, in float64       */
 } vidkv_params;
+
+/* A second stream for the calls that can use one, with the two events that
+ * fork it from and join it back into `hip_stream`.  All three are created and
+ * owned by the caller, on the device of `hip_stream`, at the default stream
+ * priority; the events may have timing disabled.  The call records fork_event
+ * on `hip_stream`, lets the side stream wait for it, enqueues part of its work
+ * there, records join_event on the side stream and lets `hip_stream` wait for
+ * it before anything that depends on that work: to the caller everything
+ * stays ordered on `hip_stream`, also under stream capture (the side stream
+ * joins the capture and leaves it again within the call).  Once the fork has
+ * been recorded the join is enqueued even if a later launch fails.  One such
+ * triple serves any number of calls that are enqueued one after another;
+ * calls that may be enqueued at the same time from different host threads need
+ * one each.  Passing NULL (or using an entry point without the argument)
+ * keeps all work in line on `hip_stream`. */
+typedef struct vidkv_side_stream {
+  void *hip_stream; /* hipStream_t, not the stream the call is enqueued on */
+  void *fork_event; /* hipEvent_t */
+  void *join_event; /* hipEvent_t */
+} vidkv_side_stream;
 
 /* Size queries: pure host functions, usable without a GPU.  Return 0 when
  * `params` is NULL or invalid.  `which`: 0 = quantize_keys, 1 = quantize_values,
@@ -151,24 +175,21 @@ vidkv_status vidkv_quantize_values(const vidkv_params *params, const void *V_dev
 /* Alg. 3 and Alg. 2 on the K and V tensors of the same tokens in one call (the
  * compression step at the end of Alg. 1, Prefill): the packed buffers come out
  * byte-identical to vidkv_quantize_keys followed by vidkv_quantize_values.
- * The protected-token selection - a chain of short dependent launches - is
- * enqueued on a side stream owned by the library (one per device, default
- * priority, created at the first call and kept until the process ends) so
- * that it runs beside the key passes (only when the key tensor is 32 MiB or
- * more; smaller inputs run in line).  The side stream starts after
- * everything already enqueued on `hip_stream` and is joined back before the
- * value coding pass: to the caller all work is ordered on `hip_stream` as
- * usual.  The stream and its two events are created at the first call that
- * needs them (make that call once outside a stream capture); fork and join
- * are plain event record / wait pairs and are captured with the rest.
+ * With a side stream the protected-token selection - a chain of short
+ * dependent launches - is enqueued there so that it runs beside the key
+ * passes (only when the key tensor is 32 MiB or more; smaller inputs run in
+ * line); it is joined back before the value coding pass.
  * Arguments as for the two separate calls;
- *   workspace_dev : >= vidkv_workspace_bytes(params, 3) bytes                 */
+ *   workspace_dev : >= vidkv_workspace_bytes(params, 3) bytes
+ *   side          : NULL, or the caller's side stream and events (all three
+ *                   handles non-NULL, else VIDKV_EINVAL)                      */
 vidkv_status vidkv_quantize_kv(const vidkv_params *params, const void *K_dev,
                                const void *V_dev, const float *saliency_dev,
                                const int32_t *salient_idx_dev, void *packed_K_dev,
                                size_t packed_K_bytes, void *packed_V_dev,
                                size_t packed_V_bytes, void *workspace_dev,
-                               size_t workspace_bytes, void *hip_stream);
+                               size_t workspace_bytes, void *hip_stream,
+                               const vidkv_side_stream *side);
 
 /* Alg. 1, Decoding, for one layer: out = Softmax(scale * q [K'; K_r]^T) [V'; V_r]
  * (Eq. 3) where K', V' are the dequantized packed tokens (never materialised
@@ -187,18 +208,18 @@ vidkv_status vidkv_quantize_kv(const vidkv_params *params, const void *K_dev,
  *                     depends on t_capacity, not on t_quant)
  * With Tq == 0 this is plain attention over the residual tokens; a sequence
  * with no token at all gets zeros.
- * A large residual block (1024 or more 32-token blocks over all sequences and
- * KV heads, at most 8 counted per head) is read by a kernel that is forked
- * onto the library's side stream (see vidkv_quantize_kv) and joined before
- * the split partials are merged; to the caller all work stays ordered on
- * `hip_stream`.                                                               */
+ * With a side stream, a large residual block (32-token blocks over all
+ * sequences and KV heads, at most 8 counted per head, numbering four times
+ * the device's compute units or more) is read by a kernel that is forked onto
+ * it and joined before the split partials are merged.
+ *   side            : NULL, or the caller's side stream and events           */
 vidkv_status vidkv_decode_attention(const vidkv_params *params, int32_t layer,
                                     const void *q_dev, const void *packed_K_dev,
                                     const void *packed_V_dev, const void *K_tail_dev,
                                     const void *V_tail_dev, int32_t tail_capacity,
                                     const int32_t *tail_len_dev, void *out_dev,
                                     void *workspace_dev, size_t workspace_bytes,
-                                    void *hip_stream);
+                                    void *hip_stream, const vidkv_side_stream *side);
 
 /* vidkv_decode_attention for callers that cannot allocate device memory or
  * carry a workspace: code under HIP graph capture, tight serving loops,
@@ -206,8 +227,8 @@ vidkv_status vidkv_decode_attention(const vidkv_params *params, int32_t layer,
  * vidkv_decode_attention, without the workspace: the split partials go to a
  * device array inside the library's image, VIDKV_NOALLOC_SCRATCH_BYTES large,
  * which every GPU that runs the library holds until the process ends.  The
- * call allocates nothing and creates no stream or event; all of its kernels,
- * the one for a large residual block included, run in line on `hip_stream`.
+ * call allocates nothing and takes no side stream: all of its kernels, the
+ * one for a large residual block included, run in line on `hip_stream`.
  * A shape whose partials (what vidkv_workspace_bytes(params, 2) reports) do
  * not fit the array returns VIDKV_ENOSPACE and launches nothing.  The device
  * address of the array is looked up at the first call on each device (make
@@ -291,7 +312,8 @@ vidkv_status vidkv_decode_attention_stages(const vidkv_params *params, int32_t l
                                            const void *V_tail_dev, int32_t tail_capacity,
                                            const int32_t *tail_len_dev, void *out_dev,
                                            void *workspace_dev, size_t workspace_bytes,
-                                           uint32_t stages, void *hip_stream);
+                                           uint32_t stages, void *hip_stream,
+                                           const vidkv_side_stream *side);
 
 /* Measurement aid, not part of the method: dst[i] = src[i] for `bytes` bytes
  * (multiple of 16, both 16-byte aligned) with the library's streaming access

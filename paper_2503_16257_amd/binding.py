@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libvidkv.so")
 OK, EINVAL, ESHAPE, ENOSPACE, EHIP = 0, 1, 2, 3, 4
 
 
-ABI_VERSION = 2          # VIDKV_ABI_VERSION of include/vidkv.h that this binding was written for
+ABI_VERSION = 3          # VIDKV_ABI_VERSION of include/vidkv.h that this binding was written for
 
 
 class VidkvParams(C.Structure):
@@ -28,6 +28,31 @@ class VidkvParams(C.Structure):
         ("n_salient", C.c_int32), ("gamma", C.c_float), ("softmax_scale", C.c_float),
         ("t_capacity", C.c_int32), ("salient_bits", C.c_int32), ("channel_metric", C.c_int32),
     ]
+
+
+class VidkvSideStream(C.Structure):
+    _fields_ = [("hip_stream", C.c_void_p), ("fork_event", C.c_void_p), ("join_event", C.c_void_p)]
+
+
+class SideStream:
+    """A torch stream and two events for the calls that take a vidkv_side_stream.
+
+    Owned by the caller: keep it alive as long as work enqueued with it may run."""
+
+    def __init__(self, device="cuda:0"):
+        import torch
+        with torch.cuda.device(device):
+            self.stream = torch.cuda.Stream(device=device)          # default priority
+            self.fork = torch.cuda.Event(enable_timing=False)
+            self.join = torch.cuda.Event(enable_timing=False)
+            # torch creates the event handle lazily, at the first record
+            self.fork.record(self.stream)
+            self.join.record(self.stream)
+        self.c = VidkvSideStream(self.stream.cuda_stream, self.fork.cuda_event, self.join.cuda_event)
+
+
+def _side(side):
+    return None if side is None else C.byref(side.c)
 
 
 class VidkvError(RuntimeError):
@@ -64,7 +89,8 @@ def lib() -> C.CDLL:
         L.vidkv_quantize_keys.restype = C.c_int
         L.vidkv_quantize_values.argtypes = [PP, vp, vp, vp, vp, sz, vp, sz, vp]
         L.vidkv_quantize_values.restype = C.c_int
-        L.vidkv_quantize_kv.argtypes = [PP, vp, vp, vp, vp, vp, sz, vp, sz, vp, sz, vp]
+        SP = C.POINTER(VidkvSideStream)
+        L.vidkv_quantize_kv.argtypes = [PP, vp, vp, vp, vp, vp, sz, vp, sz, vp, sz, vp, SP]
         L.vidkv_quantize_kv.restype = C.c_int
         L.vidkv_flush_residual.argtypes = [PP, i32, vp, vp, i32, i32, vp, sz, vp, sz, vp]
         L.vidkv_flush_residual.restype = C.c_int
@@ -72,7 +98,7 @@ def lib() -> C.CDLL:
         L.vidkv_saliency_workspace_bytes.restype = sz
         L.vidkv_saliency_scores.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, sz, vp]
         L.vidkv_saliency_scores.restype = C.c_int
-        L.vidkv_decode_attention.argtypes = [PP, i32, vp, vp, vp, vp, vp, i32, vp, vp, vp, sz, vp]
+        L.vidkv_decode_attention.argtypes = [PP, i32, vp, vp, vp, vp, vp, i32, vp, vp, vp, sz, vp, SP]
         L.vidkv_decode_attention.restype = C.c_int
         L.vidkv_decode_attention_noalloc.argtypes = [PP, i32, vp, vp, vp, vp, vp, i32, vp, vp, vp]
         L.vidkv_decode_attention_noalloc.restype = C.c_int
@@ -82,7 +108,7 @@ def lib() -> C.CDLL:
         L.vidkv_quantize_values_stages.argtypes = [PP, vp, vp, vp, vp, sz, vp, sz, u32, vp]
         L.vidkv_quantize_values_stages.restype = C.c_int
         L.vidkv_decode_attention_stages.argtypes = [PP, i32, vp, vp, vp, vp, vp, i32, vp, vp, vp,
-                                                    sz, u32, vp]
+                                                    sz, u32, vp, SP]
         L.vidkv_decode_attention_stages.restype = C.c_int
         L.vidkv_calib_copy.argtypes = [vp, vp, sz, vp]
         L.vidkv_calib_copy.restype = C.c_int
@@ -181,8 +207,9 @@ def quantize_values(p: VidkvParams, V, packed_V, workspace, saliency=None, salie
 
 def decode_attention(p: VidkvParams, layer: int, q, packed_K, packed_V, out, workspace,
                      K_tail=None, V_tail=None, tail_capacity: int = 0, tail_len=None,
-                     stream=None, stages=None) -> None:
-    """vidkv_decode_attention: one decode step of one layer -> out [B,Hq,128] fp16."""
+                     stream=None, stages=None, side=None) -> None:
+    """vidkv_decode_attention: one decode step of one layer -> out [B,Hq,128] fp16.
+    `side`: a SideStream for the residual-token kernel of a large block, or None (in line)."""
     import torch
     a = [C.byref(p), layer, _ptr(q, torch.float16, "q"), _ptr(packed_K, torch.uint8, "packed_K"),
          _ptr(packed_V, torch.uint8, "packed_V"), _ptr(K_tail, torch.float16, "K_tail"),
@@ -190,9 +217,9 @@ def decode_attention(p: VidkvParams, layer: int, q, packed_K, packed_V, out, wor
          _ptr(out, torch.float16, "out"), _ptr(workspace, torch.uint8, "workspace"),
          _nbytes(workspace)]
     if stages is None:
-        _check(lib().vidkv_decode_attention(*a, _stream(stream)), "vidkv_decode_attention")
+        _check(lib().vidkv_decode_attention(*a, _stream(stream), _side(side)), "vidkv_decode_attention")
     else:
-        _check(lib().vidkv_decode_attention_stages(*a, stages, _stream(stream)),
+        _check(lib().vidkv_decode_attention_stages(*a, stages, _stream(stream), _side(side)),
                "vidkv_decode_attention_stages")
 
 
@@ -211,15 +238,16 @@ def decode_attention_noalloc(p: VidkvParams, layer: int, q, packed_K, packed_V, 
 
 
 def quantize_kv(p: VidkvParams, K, V, packed_K, packed_V, workspace, saliency=None,
-                salient_idx=None, stream=None) -> None:
-    """vidkv_quantize_kv: both tensors of the same tokens in one call."""
+                salient_idx=None, stream=None, side=None) -> None:
+    """vidkv_quantize_kv: both tensors of the same tokens in one call.
+    `side`: a SideStream for the protected-token selection, or None (in line)."""
     import torch
     _check(lib().vidkv_quantize_kv(
         C.byref(p), _ptr(K, torch.float16, "K"), _ptr(V, torch.float16, "V"),
         _ptr(saliency, torch.float32, "saliency"), _ptr(salient_idx, torch.int32, "salient_idx"),
         _ptr(packed_K, torch.uint8, "packed_K"), _nbytes(packed_K),
         _ptr(packed_V, torch.uint8, "packed_V"), _nbytes(packed_V),
-        _ptr(workspace, torch.uint8, "workspace"), _nbytes(workspace), _stream(stream)),
+        _ptr(workspace, torch.uint8, "workspace"), _nbytes(workspace), _stream(stream), _side(side)),
         "vidkv_quantize_kv")
 
 

@@ -546,10 +546,12 @@ hipError_t launch_decode_attention(const Geom& g, int layer, float scale, const 
       if (has_tail && side) {
         if (hipEventRecord(fork, st) != hipSuccess) return hipErrorUnknown;
         if (hipStreamWaitEvent(side, fork, 0) != hipSuccess) return hipErrorUnknown;
+        // the side stream now depends on `st`: it is joined back whatever fails below
         hipLaunchKernelGGL(attn_tail_kernel, dim3(ntail, g.H, g.B), dim3(256), 0, side, a);
-        if (hipEventRecord(join, side) != hipSuccess) return hipErrorUnknown;
+        const bool rec = hipEventRecord(join, side) == hipSuccess;
         launch_attn_mfma(a, dim3(a.nsplit, g.H, g.B), st);
-        if (hipStreamWaitEvent(st, join, 0) != hipSuccess) return hipErrorUnknown;
+        const bool joined = hipStreamWaitEvent(st, join, 0) == hipSuccess;
+        if (!rec || !joined) return hipErrorUnknown;
       } else {
         launch_attn_mfma(a, dim3(a.nsplit, g.H, g.B), st);
         if (has_tail)

@@ -83,7 +83,10 @@ __global__ __launch_bounds__(256) void k_encode_mfma_kernel(const u32x4* __restr
   const int nq = n_a >> 2;
 
   __shared__ u32x4 tile4[4][32 * ENC_ROW / 16];   // per wave: the group's tile
-  __shared__ u32x4 recbuf[4][1536 / 16];          // per wave: the record being assembled
+  // per wave: the record being assembled (12 n_a + 8 n_n bytes; 1536 at most).  With n_a known
+  // the workgroup stays below a quarter of the LDS and four of them share a compute unit.
+  constexpr int RECB = NA8T >= 0 ? 12 * 8 * NA8T + 8 * (D - 8 * NA8T) : 1536;
+  __shared__ u32x4 recbuf[4][RECB / 16];
 
   // the first tile is requested before anything else so that its latency
   // overlaps the set-up below

@@ -1,5 +1,6 @@
 // C ABI of the VidKV library: argument validation on the host, then kernel
-// launches on the caller's stream.  Nothing here allocates or synchronizes.
+// launches on the caller's stream (and, for two calls, on a second stream that the
+// caller hands in).  Nothing here allocates, synchronizes, or creates streams or events.
 #include <mutex>
 
 #include "vidkv_common.h"
@@ -54,30 +55,39 @@ __global__ __launch_bounds__(256) void calib_copy_kernel(const u32x4* __restrict
 
 using namespace vidkv;
 
-// Per-device side stream and fork / join events of vidkv_quantize_kv, created on
-// first use and kept until the process ends.
 namespace {
-struct SideStream {
+constexpr int MAX_DEVICES = 64;
+
+// The caller's side stream and events, or nothing.  All three handles must be there.
+struct Side {
   hipStream_t stream = nullptr;
   hipEvent_t fork = nullptr, join = nullptr;
-  bool ready = false;
+  bool ok = false;
 };
-constexpr int MAX_DEVICES = 64;
-SideStream g_side[MAX_DEVICES];
-std::mutex g_side_mutex;
-
-SideStream* side_stream_locked() {
-  int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return nullptr;
-  SideStream& s = g_side[dev];
-  if (!s.ready) {
-    // default priority, like every stream this library touches
-    if (hipStreamCreateWithFlags(&s.stream, hipStreamNonBlocking) != hipSuccess) return nullptr;
-    if (hipEventCreateWithFlags(&s.fork, hipEventDisableTiming) != hipSuccess) return nullptr;
-    if (hipEventCreateWithFlags(&s.join, hipEventDisableTiming) != hipSuccess) return nullptr;
-    s.ready = true;
+Side take_side(const vidkv_side_stream* s) {
+  Side r;
+  if (s && s->hip_stream && s->fork_event && s->join_event) {
+    r.stream = static_cast<hipStream_t>(s->hip_stream);
+    r.fork = static_cast<hipEvent_t>(s->fork_event);
+    r.join = static_cast<hipEvent_t>(s->join_event);
+    r.ok = true;
   }
-  return &s;
+  return r;
+}
+bool side_malformed(const vidkv_side_stream* s) {
+  return s && !(s->hip_stream && s->fork_event && s->join_event);
+}
+
+// A stream of another device than the current one cannot take this call's launches.
+// (The NULL stream belongs to the current device.  If the runtime cannot tell, go on.)
+bool stream_on_current_device(hipStream_t st) {
+  if (!st) return true;
+  int cur = 0, dev = 0;
+  if (hipGetDevice(&cur) != hipSuccess || hipStreamGetDevice(st, &dev) != hipSuccess) {
+    (void)hipGetLastError();
+    return true;
+  }
+  return cur == dev;
 }
 }  // namespace
 
@@ -157,9 +167,10 @@ vidkv_status vidkv_quantize_values(const vidkv_params* p, const void* V, const f
 vidkv_status vidkv_quantize_kv(const vidkv_params* p, const void* K, const void* V,
                                const float* saliency, const int32_t* salient_idx, void* packed_K,
                                size_t packed_K_bytes, void* packed_V, size_t packed_V_bytes,
-                               void* ws, size_t ws_bytes, void* stream) {
+                               void* ws, size_t ws_bytes, void* stream,
+                               const vidkv_side_stream* side) {
   Geom g;
-  if (!p || !packed_K || !packed_V || !ws) return VIDKV_EINVAL;
+  if (!p || !packed_K || !packed_V || !ws || side_malformed(side)) return VIDKV_EINVAL;
   if (!make_geom(p, &g)) return VIDKV_ESHAPE;
   if (g.T > 0 && (!K || !V)) return VIDKV_EINVAL;
   if (g.nheads > 65535) return VIDKV_ESHAPE;
@@ -177,21 +188,26 @@ vidkv_status vidkv_quantize_kv(const vidkv_params* p, const void* K, const void*
   void* ws_v = static_cast<uint8_t*>(ws) + ws_keys(g);
   const float* sc = g.n_s > 0 ? saliency : nullptr;
   const int32_t* ix = g.n_s > 0 ? salient_idx : nullptr;
-  // The fork and join cost about as much as three short launches, so the side stream pays
-  // only when the key passes are long enough to hide the selection chain behind them.
-  const bool fork = (size_t)g.nheads * g.T * D * 2 >= ((size_t)32 << 20);
+  if (!stream_on_current_device(st)) return VIDKV_EINVAL;
+  // The chain of short dependent launches that selects the protected tokens runs on the side
+  // stream beside the bandwidth-bound key passes.  The fork and join cost about as much as
+  // three short launches, so this pays only when the key passes are long enough to hide the
+  // chain behind them.  (Moving the channel selection over as well, beside the value coding
+  // pass, was measured and lost: its four large workgroups wait for free compute units until
+  // the coding pass has been dispatched, and the second fork and join come on top.)
+  const Side sd = take_side(side);
+  const bool fork = sd.ok && (size_t)g.nheads * g.T * D * 2 >= ((size_t)32 << 20);
   if (g.n_s > 0 && g.T > 0 && fork) {
-    // the chain of short selection launches runs beside the bandwidth-bound key passes
-    std::lock_guard<std::mutex> lock(g_side_mutex);
-    SideStream* s = side_stream_locked();
-    if (!s) return VIDKV_EHIP;
-    if (hipEventRecord(s->fork, st) != hipSuccess) return VIDKV_EHIP;
-    if (hipStreamWaitEvent(s->stream, s->fork, 0) != hipSuccess) return VIDKV_EHIP;
-    if (launch_quantize_values(g, p->gamma, V, sc, ix, pv, ws_v, 1u, s->stream) != hipSuccess)
-      return VIDKV_EHIP;
-    if (hipEventRecord(s->join, s->stream) != hipSuccess) return VIDKV_EHIP;
-    if (launch_quantize_keys(g, K, pk, ws_k, ~0u, st) != hipSuccess) return VIDKV_EHIP;
-    if (hipStreamWaitEvent(st, s->join, 0) != hipSuccess) return VIDKV_EHIP;
+    if (!stream_on_current_device(sd.stream)) return VIDKV_EINVAL;
+    if (hipEventRecord(sd.fork, st) != hipSuccess) return VIDKV_EHIP;
+    if (hipStreamWaitEvent(sd.stream, sd.fork, 0) != hipSuccess) return VIDKV_EHIP;
+    // from here on the side stream depends on `st`: whatever fails, it is joined back, so
+    // that a stream capture on `st` can still be ended
+    bool good = launch_quantize_values(g, p->gamma, V, sc, ix, pv, ws_v, 1u, sd.stream) == hipSuccess;
+    good = (hipEventRecord(sd.join, sd.stream) == hipSuccess) && good;
+    good = good && launch_quantize_keys(g, K, pk, ws_k, ~0u, st) == hipSuccess;
+    good = (hipStreamWaitEvent(st, sd.join, 0) == hipSuccess) && good;
+    if (!good) return VIDKV_EHIP;
     return launch_quantize_values(g, p->gamma, V, sc, ix, pv, ws_v, 2u, st) == hipSuccess
                ? VIDKV_OK : VIDKV_EHIP;
   }
@@ -224,9 +240,9 @@ vidkv_status vidkv_decode_attention_stages(const vidkv_params* p, int32_t layer,
                                            const void* K_tail, const void* V_tail,
                                            int32_t tail_capacity, const int32_t* tail_len,
                                            void* out, void* ws, size_t ws_bytes, uint32_t stages,
-                                           void* stream) {
+                                           void* stream, const vidkv_side_stream* side) {
   Geom g;
-  if (!ws) return VIDKV_EINVAL;
+  if (!ws || side_malformed(side)) return VIDKV_EINVAL;
   const vidkv_status chk = check_decode(p, &g, layer, q, packed_K, packed_V, K_tail, V_tail,
                                         tail_capacity, tail_len, out);
   if (chk != VIDKV_OK) return chk;
@@ -235,13 +251,13 @@ vidkv_status vidkv_decode_attention_stages(const vidkv_params* p, int32_t layer,
   const uint8_t* pk = static_cast<const uint8_t*>(packed_K);
   const uint8_t* pv = static_cast<const uint8_t*>(packed_V);
   hipStream_t st = static_cast<hipStream_t>(stream);
-  if (K_tail && V_tail && tail_len && (stages & 1u) && attn_tail_beside(g, tail_capacity)) {
-    std::lock_guard<std::mutex> lock(g_side_mutex);
-    SideStream* s = side_stream_locked();
-    if (!s) return VIDKV_EHIP;
+  if (!stream_on_current_device(st)) return VIDKV_EINVAL;
+  const Side sd = take_side(side);
+  if (sd.ok && K_tail && V_tail && tail_len && (stages & 1u) && attn_tail_beside(g, tail_capacity)) {
+    if (!stream_on_current_device(sd.stream)) return VIDKV_EINVAL;
     return launch_decode_attention(g, layer, p->softmax_scale, q, pk, pv, K_tail, V_tail,
-                                   tail_capacity, tail_len, out, ws, stages, st, s->stream,
-                                   s->fork, s->join) == hipSuccess ? VIDKV_OK : VIDKV_EHIP;
+                                   tail_capacity, tail_len, out, ws, stages, st, sd.stream,
+                                   sd.fork, sd.join) == hipSuccess ? VIDKV_OK : VIDKV_EHIP;
   }
   const hipError_t e = launch_decode_attention(g, layer, p->softmax_scale, q, pk, pv, K_tail, V_tail,
                                                tail_capacity, tail_len, out, ws, stages, st,
@@ -253,9 +269,9 @@ vidkv_status vidkv_decode_attention(const vidkv_params* p, int32_t layer, const 
                                     const void* packed_K, const void* packed_V, const void* K_tail,
                                     const void* V_tail, int32_t tail_capacity,
                                     const int32_t* tail_len, void* out, void* ws, size_t ws_bytes,
-                                    void* stream) {
+                                    void* stream, const vidkv_side_stream* side) {
   return vidkv_decode_attention_stages(p, layer, q, packed_K, packed_V, K_tail, V_tail,
-                                       tail_capacity, tail_len, out, ws, ws_bytes, ~0u, stream);
+                                       tail_capacity, tail_len, out, ws, ws_bytes, ~0u, stream, side);
 }
 
 }  // extern "C"
@@ -300,8 +316,8 @@ vidkv_status vidkv_decode_attention_noalloc(const vidkv_params* p, int32_t layer
   if (ws_attn(g) > (size_t)VIDKV_NOALLOC_SCRATCH_BYTES) return VIDKV_ENOSPACE;
   void* ws = scratch_on_current_device();
   if (!ws) return VIDKV_EHIP;
-  // Everything runs in line on the caller's stream (the side stream of the other entry point
-  // would have to be created).  Nothing in the array has to start at zero: the merge reads
+  if (!stream_on_current_device(static_cast<hipStream_t>(stream))) return VIDKV_EINVAL;
+  // Everything runs in line on the caller's stream.  Nothing in the array has to start at zero: the merge reads
   // only the parts that this call's kernels wrote before it.
   const hipError_t e = launch_decode_attention(
       g, layer, p->softmax_scale, q, static_cast<const uint8_t*>(packed_K),

@@ -28,7 +28,7 @@ def test_library_exports_every_declared_symbol():
     L = C.CDLL(vk.LIB_PATH)
     for n in names:
         assert hasattr(L, n), n
-    assert vk.abi_version() == 2
+    assert vk.abi_version() == vk.ABI_VERSION == 3
     assert vk.status_string(0) == "ok" and vk.status_string(3) == "buffer too small"
 
 
@@ -97,16 +97,19 @@ def test_entry_points_refuse_bad_arguments_before_launch():
     neg = vk.make_params(1, 1, 4, 28, 64, 16, 4, gamma=-0.5)
     assert L.vidkv_quantize_values(C.byref(neg), A, A, None, A, big, A, big, None) == vk.EINVAL
     # quantize_kv: the checks of both, and a workspace that holds both
-    assert L.vidkv_quantize_kv(pb, A, A, A, None, A, big, A, big, None, big, None) == vk.EINVAL
-    assert L.vidkv_quantize_kv(pb, None, A, A, None, A, big, A, big, A, big, None) == vk.EINVAL
-    assert L.vidkv_quantize_kv(pb, A, A, A, A, A, big, A, big, A, big, None) == vk.EINVAL
-    assert L.vidkv_quantize_kv(pb, A, A, A, None, A, kb - 1, A, big, A, big, None) == vk.ENOSPACE
-    assert L.vidkv_quantize_kv(pb, A, A, A, None, A, big, A, vb - 1, A, big, None) == vk.ENOSPACE
+    assert L.vidkv_quantize_kv(pb, A, A, A, None, A, big, A, big, None, big, None, None) == vk.EINVAL
+    assert L.vidkv_quantize_kv(pb, None, A, A, None, A, big, A, big, A, big, None, None) == vk.EINVAL
+    assert L.vidkv_quantize_kv(pb, A, A, A, A, A, big, A, big, A, big, None, None) == vk.EINVAL
+    assert L.vidkv_quantize_kv(pb, A, A, A, None, A, kb - 1, A, big, A, big, None, None) == vk.ENOSPACE
+    assert L.vidkv_quantize_kv(pb, A, A, A, None, A, big, A, vb - 1, A, big, None, None) == vk.ENOSPACE
     assert vk.workspace_bytes(p, 3) == vk.workspace_bytes(p, 0) + vk.workspace_bytes(p, 1)
     assert L.vidkv_quantize_kv(pb, A, A, A, None, A, big, A, big, A,
-                               vk.workspace_bytes(p, 3) - 1, None) == vk.ENOSPACE
+                               vk.workspace_bytes(p, 3) - 1, None, None) == vk.ENOSPACE
+    # a side stream with a handle missing is refused
+    half = vk.VidkvSideStream(A, None, A)
+    assert L.vidkv_quantize_kv(pb, A, A, A, None, A, big, A, big, A, big, None, C.byref(half)) == vk.EINVAL
     # decode_attention
-    args = [pb, 0, A, A, A, None, None, 0, None, A, A, big, None]
+    args = [pb, 0, A, A, A, None, None, 0, None, A, A, big, None, None]
     def call(**kw):
         a = list(args)
         for k, v in kw.items():
@@ -120,6 +123,7 @@ def test_entry_points_refuse_bad_arguments_before_launch():
     assert call(a11=vk.workspace_bytes(p, 2) - 1) == vk.ENOSPACE
     noscale = vk.make_params(1, 1, 4, 28, 64, 16, 4, softmax_scale=0.0)
     assert call(a0=C.byref(noscale)) == vk.EINVAL
+    assert call(a13=C.byref(half)) == vk.EINVAL
     # the variant without a workspace: same checks, and a shape whose split partials exceed
     # the library's own array is refused before anything touches the GPU
     na = [pb, 0, A, A, A, None, None, 0, None, A, None]

@@ -87,12 +87,12 @@ def test_large_residual_block_forked_inside_the_capture():
 
     def step():
         vk.decode_attention(run.p, 0, q, run.pk, run.pv, out, ws, K_tail=Kt, V_tail=Vt,
-                            tail_capacity=cap, tail_len=tl)
+                            tail_capacity=cap, tail_len=tl, side=P.side_stream(DEV))
 
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
     with torch.cuda.stream(side):
-        step()                                              # warm-up creates the side stream
+        step()                                              # warm-up, outside the capture
     torch.cuda.current_stream().wait_stream(side)
     torch.cuda.synchronize()
     g = torch.cuda.CUDAGraph()
@@ -119,7 +119,7 @@ def test_large_residual_block_forked_inside_the_capture():
 
 
 def test_quantizer_with_its_side_stream_captured_and_replayed():
-    """vidkv_quantize_kv forks the protected-token selection onto the library's side stream;
+    """vidkv_quantize_kv forks the protected-token selection onto the caller's side stream;
     captured, every replay must write the same bytes as the eager call."""
     w = synth.reduced(synth.WORKLOADS["c4_long"], 176)       # 35 MB of keys: large enough to fork
     print("[case] graph-quantize", flush=True)
@@ -131,13 +131,13 @@ def test_quantizer_with_its_side_stream_captured_and_replayed():
     pk0, pv0 = torch.zeros_like(pk), torch.zeros_like(pv)
 
     def step(dk, dv):
-        vk.quantize_kv(run.p, run.K, run.V, dk, dv, ws, saliency=sal)
+        vk.quantize_kv(run.p, run.K, run.V, dk, dv, ws, saliency=sal, side=P.side_stream(DEV))
 
     pk0.zero_(); pv0.zero_()
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
     with torch.cuda.stream(side):
-        step(pk0, pv0)                                      # eager; also creates the side stream
+        step(pk0, pv0)                                      # eager
     torch.cuda.current_stream().wait_stream(side)
     torch.cuda.synchronize()
     g = torch.cuda.CUDAGraph()

@@ -83,7 +83,7 @@ def test_index_list_equals_score_selection():
 @pytest.mark.parametrize("case", ["long_scores", "long_indices", "layer_no_protection", "serving_batch",
                                   "two_bit_rows_one_bit_keys"])
 def test_fused_quantizer_equals_separate_calls(case):
-    """vidkv_quantize_kv (selection on the library's side stream) writes the same bytes as
+    """vidkv_quantize_kv (selection on a side stream of the caller) writes the same bytes as
     the two separate calls, on the default and on a caller's stream, call after call."""
     kw = {}
     if case.startswith("long"):
@@ -174,8 +174,9 @@ def test_one_long_head_many_split_parts():
 
 
 def test_large_residual_block_with_ragged_lengths():
-    """A batch whose residual block is large enough to be read on the library's side stream,
-    with lengths from 0 to the capacity: sampled sequences against the oracle."""
+    """A batch whose residual block is large enough to be read on the caller's side stream,
+    with lengths from 0 to the capacity: sampled sequences against the oracle, and the same
+    call without a side stream (all in line) bit for bit."""
     w = synth.reduced(synth.WORKLOADS["c5_serving"], 8, B=32)
     print("[case] forked residual block, ragged", flush=True)
     run = P.GpuRun(w, DEV)
@@ -187,6 +188,9 @@ def test_large_residual_block_with_ragged_lengths():
     tl_np[0], tl_np[1], tl_np[2] = 0, cap, 1
     tl = torch.from_numpy(tl_np).to(DEV)
     out = run.attention(0, torch.from_numpy(q).to(DEV), Ktd, Vtd, cap, tl).cpu().numpy()
+    run.use_side = False
+    inline = run.attention(0, torch.from_numpy(q).to(DEV), Ktd, Vtd, cap, tl).cpu().numpy()
+    assert np.array_equal(out.view(np.uint16), inline.view(np.uint16))
     for b in (0, 1, 2, 17, 31):
         n = int(tl_np[b])
         ref = P.oracle_attention(run, 0, b, q[b], Kt[b][:, :n], Vt[b][:, :n])

@@ -41,13 +41,14 @@ def test_long_video_full_size(mode):
     run = P.GpuRun(w, DEV, K=K, V=V, saliency=torch.from_numpy(scores).to(DEV),
                    use_fft=0 if alt else 1, salient_bits=2 if alt else 0,
                    t_capacity=w.T + 128 if alt else 0)
-    _check_heads(run, K, V, [0, 3], scores)
-    print("[step] codec ok", flush=True)
+    heads = list(range(w.n_heads))                           # all 4 KV heads
+    _check_heads(run, K, V, heads, scores)
+    print(f"[step] codec ok on {len(heads)} of {w.n_heads} heads", flush=True)
     q = synth.query(w, 0)
     out = run.attention(0, torch.from_numpy(q).to(DEV)).cpu().numpy()
     ref = P.oracle_attention(run, 0, 0, q[0])
     err = P.assert_out_close(out[0], ref, "c4_long")
-    print(f"[step] attention ok, max err {err:.2e}", flush=True)
+    print(f"[step] attention ok on all {w.Hq} query heads, max err {err:.2e}", flush=True)
     if alt:
         import test_gpu_flush as F
         Kt = np.stack([synth.tail_heads(w, 0, b, 128)[0] for b in range(w.B)])
@@ -55,7 +56,7 @@ def test_long_video_full_size(mode):
         run.flush(0, torch.from_numpy(Kt).to(DEV), torch.from_numpy(Vt).to(DEV), 128, 128)
         run.advance(128)
         stats = {}
-        for h in (0, 3):
+        for h in range(w.Hkv):
             F._check_block(run, h, w.T // 32, Kt[0, h], Vt[0, h], stats)
         P.check_near_budget(stats)
         q = synth.query(w, 0, step=1)
@@ -70,15 +71,20 @@ def test_full_stack_16_decode_steps():
     print("[case] c3_stack full", flush=True)
     K, V = synth.device_kv(w, DEV)
     run = P.GpuRun(w, DEV, K=K, V=V)
-    _check_heads(run, K, V, [0, 449, w.n_heads - 1], None)
-    print("[step] codec ok", flush=True)
+    # one head of every layer, the sequence and KV head moving with the layer
+    heads = [(l * w.B + (3 * l + 1) % w.B) * w.Hkv + (l % w.Hkv) for l in range(w.L)]
+    heads[0], heads[-1] = 0, w.n_heads - 1
+    _check_heads(run, K, V, heads, None)
+    print(f"[step] codec ok on {len(heads)} heads, one per layer", flush=True)
     del K, V
     cap = 16
     # residual buffers of every layer: [L][B, Hkv, cap, 128]
     Kt = torch.zeros((w.L, w.B, w.Hkv, cap, 128), dtype=torch.float16, device=DEV)
     Vt = torch.zeros_like(Kt)
     tl = torch.zeros((w.B,), dtype=torch.int32, device=DEV)
-    sample = [(0, 0), (13, 5), (27, 7)]                       # (layer, sequence) checked by the oracle
+    # (layer, sequence) pairs checked by the oracle: every layer, the sequence moving with it
+    sample = [(l, (5 * l + 2) % w.B) for l in range(w.L)]
+    sample[0], sample[-1] = (0, 0), (w.L - 1, w.B - 1)
     gen = torch.Generator(device=DEV); gen.manual_seed(77)
     for step in range(w.decode_steps):
         newk = torch.randn((w.L, w.B, w.Hkv, 128), generator=gen, device=DEV).to(torch.float16)
@@ -99,7 +105,7 @@ def test_full_stack_16_decode_steps():
                                          Kt[layer, b, :, :step + 1].cpu().numpy(),
                                          Vt[layer, b, :, :step + 1].cpu().numpy())
                 P.assert_out_close(o[b].cpu().numpy(), ref, f"c3 step {step} layer {layer} seq {b}")
-            print(f"[step] decode step {step} ok", flush=True)
+            print(f"[step] decode step {step} ok on {len(sample)} (layer, sequence) pairs", flush=True)
 
 
 @pytest.mark.parametrize("w", synth.serving_sweep(), ids=lambda w: w.name)
@@ -110,7 +116,11 @@ def test_serving_sweep_full_size(w):
     scores = synth.saliency(w) if w.n_salient else None
     run = P.GpuRun(w, DEV, K=K, V=V,
                    saliency=None if scores is None else torch.from_numpy(scores).to(DEV))
-    _check_heads(run, K, V, [1, w.n_heads - 2], scores)
+    # 8 heads: the first and last sequence, and others with the KV head moving
+    heads = [0, 1 * w.Hkv + 1, 9 * w.Hkv + 2, 22 * w.Hkv + 3, 37 * w.Hkv, 50 * w.Hkv + 1,
+             (w.B - 1) * w.Hkv + 2, w.n_heads - 1]
+    _check_heads(run, K, V, heads, scores)
+    print(f"[step] codec ok on {len(heads)} heads", flush=True)
     del K, V
     q = synth.query(w, 0)
     gen = torch.Generator(device=DEV); gen.manual_seed(5)
@@ -119,7 +129,10 @@ def test_serving_sweep_full_size(w):
     tl_np = np.full(w.B, w.T_tail, dtype=np.int32); tl_np[1] = 100
     out = run.attention(0, torch.from_numpy(q).to(DEV), Kt, Vt, w.T_tail,
                         torch.from_numpy(tl_np).to(DEV)).cpu().numpy()
-    for b in (0, 1, w.B - 1):
+    seqs = (0, 1, 7, 18, 29, 41, 52, w.B - 1)              # sequence 1 has the short tail
+    worst = 0.0
+    for b in seqs:
         ref = P.oracle_attention(run, 0, b, q[b], Kt[b, :, :tl_np[b]].cpu().numpy(),
                                  Vt[b, :, :tl_np[b]].cpu().numpy())
-        P.assert_out_close(out[b], ref, f"{w.name} seq {b}")
+        worst = max(worst, P.assert_out_close(out[b], ref, f"{w.name} seq {b}"))
+    print(f"[step] attention ok on {len(seqs)} sequences, max err {worst:.2e}", flush=True)

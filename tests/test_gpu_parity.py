@@ -158,6 +158,30 @@ def test_gqa_ratios_batch_and_layers(Hkv, Hq):
             P.assert_out_close(out[b], ref, f"gqa {Hkv}/{Hq} l{layer} b{b}")
 
 
+def test_values_eight_times_larger_scale_the_error_with_them():
+    """Pins the error model of the attention output: every term of the error is a relative
+    error of a probability or of a value, so with V scaled by 8 the absolute error may grow 8
+    times and no more (the probabilities entering the numerator and the denominator are the
+    same rounded numbers, so no bias adds to it)."""
+    w = synth.reduced(synth.WORKLOADS["c4_long"], 24)
+    print("[case] values x8", flush=True)
+    K = torch.from_numpy(np.stack([synth.key_head(w, hd) for hd in range(w.n_heads)])
+                         .reshape(w.L, w.B, w.Hkv, w.T, 128)).to(DEV)
+    V1 = np.stack([synth.value_head(w, hd) for hd in range(w.n_heads)]).reshape(w.L, w.B, w.Hkv, w.T, 128)
+    q = synth.query(w, 0)
+    errs = []
+    for scale in (1.0, 8.0):
+        V = torch.from_numpy((V1.astype(np.float32) * scale).astype(np.float16)).to(DEV)
+        run = P.GpuRun(w, DEV, K=K, V=V)
+        out = run.attention(0, torch.from_numpy(q).to(DEV)).cpu().numpy()
+        ref = P.oracle_attention(run, 0, 0, q[0])
+        err = np.abs(out[0].astype(np.float64) - ref).max()
+        assert np.isfinite(out).all()
+        assert err <= scale * P.ATOL_OUT, f"values x{scale}: max abs err {err:.3e}"
+        errs.append(err)
+    print(f"[step] max err {errs[0]:.2e} at x1, {errs[1]:.2e} at x8", flush=True)
+
+
 def test_one_long_head_many_split_parts():
     """One KV head with a long sequence: the split count goes far above what the
     one-round merge takes, so the general merge kernel is the one checked here."""

@@ -42,7 +42,20 @@ from __future__ import annotations
 import numpy as np
 
 G = 32          # group size along tokens (Sec. 4.1)
-BAND = 1e-6     # width of the exclusion band around decision thresholds
+# Exclusion bands around the decision thresholds.  An element closer to its threshold than
+# the band is flagged `near`: a correct float32 evaluation of the same formula may decide it
+# the other way, so a comparison against such an evaluation leaves it out (and counts it).
+# Each width is the worst-case rounding error of ANY float32 evaluation order, u = 2^-24:
+#   Eq. 4 codes : (x - z) * (levels / (max - z)) is four rounded operations on a number of at
+#                 most `levels` = 3 steps: 3 * 4u = 7.2e-7 steps.
+#   Eq. 5 signs : a 32-term sum whose every term may be split in up to three exact partial
+#                 products, i.e. at most 95 rounded additions of terms bounded by |x_t|:
+#                 95u * sum|x| = 5.7e-6 * sum|x|.
+#   Eq. 6 trits : mean |V| is a sum of at most 32 non-negative terms (31 additions), a
+#                 division by the count and a product with gamma: 33u = 2.0e-6, relative.
+BAND = 1e-6          # Eq. 4, in quantization steps
+BAND_SIGN = 6e-6     # Eq. 5, times the group's sum |x|
+BAND_TRIT = 2.5e-6   # Eq. 6, times the threshold alpha
 
 
 # --------------------------------------------------------------------------
@@ -165,7 +178,7 @@ def fft1bit_quant(x16: np.ndarray):
     s_re = np.abs(re).mean(axis=2)
     s_im = np.abs(im).mean(axis=2)
     l1 = np.abs(x).sum(axis=1)                                     # [g, c]
-    near = np.abs(coef) < BAND * l1[..., None]
+    near = np.abs(coef) < BAND_SIGN * l1[..., None]
     return {
         "bits": bits,
         "sre16": s_re.astype(np.float16),
@@ -306,7 +319,7 @@ def ternary_quant(V16: np.ndarray, salient_idx: np.ndarray, gamma: float):
     codes[x > alpha[..., None]] = 1
     codes[x < -alpha[..., None]] = -1
     codes[np.broadcast_to(~m, codes.shape)] = 0
-    near = np.abs(np.abs(x) - alpha[..., None]) < BAND * alpha[..., None]
+    near = np.abs(np.abs(x) - alpha[..., None]) < BAND_TRIT * alpha[..., None]
     near &= np.broadcast_to(m, near.shape)
     return {
         "codes": codes,

@@ -9,12 +9,14 @@
 //     permutation, its channel at its 8 token slots with 16-bit LDS loads that
 //     fill register halves directly: the MFMA operand of a contraction over
 //     tokens, gathered and transposed for free.
-//  3. Normal channels: X (16 channels x 32 tokens) times the DFT matrix, split
-//     in three fp16 parts (exact products, fp32 accumulation), in both
-//     orientations: [channel][slot] gives each lane 4 channels of one
-//     coefficient -> sign bits land in the record's word order with one lane
-//     swap; [slot][channel] gives each lane 8 coefficients of one channel
-//     -> the mean-|.| scales need only a 4-lane sum.
+//  3. Normal channels: the DFT matrix, split in three fp16 parts (exact products,
+//     fp32 accumulation), times X (32 tokens x 16 channels), as [slot][channel]:
+//     each lane gets 8 coefficients of one channel, so the mean-|.| scales need
+//     only a 4-lane sum, and a wave-wide ballot of "coefficient >= 0" per
+//     accumulator register holds, byte by byte, the record's sign words (8
+//     channels of one slot per byte).  One orientation serves both: the key
+//     coding pass is limited by what the SIMDs can sustain, not by HBM alone, and
+//     a second orientation for the sign bits cost 40 % more MFMA work.
 //  4. Anomalous channels: min / max over the 32 tokens, codes, 4 channels per
 //     byte assembled inside lane quads.
 // The record is assembled in LDS and written with 16-byte stores.
@@ -250,26 +252,31 @@ __global__ __launch_bounds__(256) void k_encode_mfma_kernel(const u32x4* __restr
         // ---------------- Eq. 5: 32-point DFT along tokens, sign bits and mean-|.| scales
         const int jn = j - NTa;
         const f4 zero = f4{0.f, 0.f, 0.f, 0.f};
-        // [channel][slot]: my column = slot x16, my rows = channels 4kb + i of the tile
-        f4 sRe = mma(X, F[0][0], zero), sIm = mma(X, F[1][0], zero);
-        sRe = mma(X, F[0][1], sRe);  sIm = mma(X, F[1][1], sIm);
-        sRe = mma(X, F[0][2], sRe);  sIm = mma(X, F[1][2], sIm);
-        // [slot][channel]: my column = channel x16, my rows = slots 4kb + i
+        // [slot][channel]: my column = channel x16, my rows = slots 4kb + i of the two slot
+        // tiles (Re X[0..15]; Re X[16], Im X[1..15]); three exact partial products each
         f4 aRe = mma(F[0][0], X, zero), aIm = mma(F[1][0], X, zero);
         aRe = mma(F[0][1], X, aRe);  aIm = mma(F[1][1], X, aIm);
-        // sign bits: shift in the IEEE sign of each value, then invert (bit = coef >= 0)
-        uint32_t nb = 0;
+        aRe = mma(F[0][2], X, aRe);  aIm = mma(F[1][2], X, aIm);
+        const int nidx = 16 * jn + x16;              // normal index of my column
+        // sign bits (bit = coefficient >= 0): ballot i, bit 16 kb + 8 h + e = channel
+        // 8 (2 jn + h) + e at slot 4 kb + i
+        unsigned long long bre[4], bim[4];
 #pragma unroll
-        for (int i = 3; i >= 0; --i) nb = __builtin_amdgcn_alignbit(nb, __float_as_uint(sIm[i]), 31);
-#pragma unroll
-        for (int i = 3; i >= 0; --i) nb = __builtin_amdgcn_alignbit(nb, __float_as_uint(sRe[i]), 31);
-        nb = ~nb & 0xFFu;                           // bits 0-3: Re of channels 4kb+i, bits 4-7: Im
-        // even lane groups hold channels e = 0-3 of a block, odd ones e = 4-7
-        auto nx = __builtin_amdgcn_permlane16_swap(nb, nb, false, false);
-        const uint32_t l4 = nx[0], h4 = nx[1];
-        const uint32_t w16 = (l4 & 0xFu) | ((h4 & 0xFu) << 4) | ((l4 >> 4) << 8) | ((h4 >> 4) << 12);
-        const int blk = 2 * jn + (kb >> 1);
-        if ((kb & 1) == 0 && blk < nblk) rec16[bits_h + blk * 16 + x16] = (uint16_t)w16;
+        for (int i = 0; i < 4; ++i) {
+          bre[i] = __ballot(nidx < n_n && aRe[i] >= 0.0f);
+          bim[i] = __ballot(nidx < n_n && aIm[i] >= 0.0f);
+        }
+        // lane (h = lane / 16, k = lane % 16) < 32 assembles word (blk 2 jn + h, k): low byte
+        // = first slot tile at slot k = (k / 4, k % 4), high byte = second slot tile
+        {
+          const int k = x16, h = kb & 1, ii = k & 3;
+          const unsigned long long lo8 = ii == 0 ? bre[0] : ii == 1 ? bre[1] : ii == 2 ? bre[2] : bre[3];
+          const unsigned long long hi8 = ii == 0 ? bim[0] : ii == 1 ? bim[1] : ii == 2 ? bim[2] : bim[3];
+          const int sh = 8 * (2 * (k >> 2) + h);
+          const uint32_t w16 = (uint32_t)((lo8 >> sh) & 0xFFull) | ((uint32_t)((hi8 >> sh) & 0xFFull) << 8);
+          const int blk = 2 * jn + h;
+          if (kb < 2 && blk < nblk) rec16[bits_h + blk * 16 + k] = (uint16_t)w16;
+        }
         // scales: Re X[16] sits in row 0 of the second tile and counts for the real view
         float sr = fabsf(aRe[0]) + fabsf(aRe[1]) + fabsf(aRe[2]) + fabsf(aRe[3]);
         float si = fabsf(aIm[0]) + fabsf(aIm[1]) + fabsf(aIm[2]) + fabsf(aIm[3]);
@@ -279,7 +286,6 @@ __global__ __launch_bounds__(256) void k_encode_mfma_kernel(const u32x4* __restr
         const float t2 = __uint_as_float(r32[0]) + __uint_as_float(r32[1]);
         auto r16 = __builtin_amdgcn_permlane16_swap(__float_as_uint(t2), __float_as_uint(t2), false, false);
         const float tot = (__uint_as_float(r16[0]) + __uint_as_float(r16[1])) * (1.0f / 1024.0f);
-        const int nidx = 16 * jn + x16;              // normal index of my column
         if ((kb & 1) == 0 && nidx < n_n) {
           const int b8 = nidx >> 3, e = nidx & 7;
           reinterpret_cast<_Float16*>(rec16)[meta_h + (b8 * 2 + (kb >> 1)) * 8 + e] = (_Float16)tot;

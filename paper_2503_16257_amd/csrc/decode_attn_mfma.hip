@@ -25,11 +25,35 @@
 // compute unit - so the work is split: the key operands, which also carry their
 // scale, are expanded on the ALU, the value operands through the table.
 //
-// Key and value records go from memory straight into a per-wave LDS ring, one
-// pair ahead (global_load_lds_dwordx4; lane l of a wave-wide transfer lands at
-// M0 + 16 l, i.e. a record keeps its byte order).  The compiler is not told
-// about these LDS writes: the wait that precedes the first read of a ring stage
-// is written out, and it is a wait for every outstanding load of the wave.
+// Key and value records - and protected fp16 rows, four per instruction - go
+// from memory straight into a per-wave LDS ring, one pair ahead
+// (global_load_lds_dwordx4; lane l of a wave-wide transfer lands at M0 + 16 l,
+// i.e. a record keeps its byte order; the two records of a pair are neighbours
+// in memory and in the ring, so one run of 1 KB transfers covers both).
+//
+// Two-stage software pipeline per wave: while the keys of pair p are scored,
+// the values of pair p - 4 (the wave's previous pair) are multiplied by the
+// probabilities that the previous step left in registers, as one interleaved
+// instruction stream; the ring holds two key stages and two value stages.
+//
+// What orders the hand-offs through LDS.  Every ring, row and probability
+// buffer is private to one wave, so no barrier is involved after the set-up
+// (whose two __syncthreads order the shared tables, q and the permutation).
+//   * transfer -> read: the compiler is not told that the transfer
+//     instructions write LDS.  Each step begins with a written-out
+//     "s_waitcnt vmcnt(0)" carrying a memory clobber: every transfer the wave
+//     has issued - they were all issued in the previous step - has landed, and
+//     no LDS read of the step can be moved above it.
+//   * read -> overwrite: a stage is refilled by transfers issued only after
+//     the step that read it has consumed the data in registers (the loads'
+//     results are used, so their lgkmcnt waits have passed), and the transfer
+//     statements carry a memory clobber, so the compiler keeps program order.
+//   * probabilities and rescale factors staged with ordinary LDS stores are
+//     read back by the same wave through ordinary loads: the compiler sees
+//     both and inserts the lgkmcnt waits itself; LDS executes a wave's
+//     operations in order.
+// M0 is written inside the transfer statement and named in its clobber list;
+// the kernel has no other user of M0.
 //
 // Softmax is online in the exp2 domain with a lazily raised running maximum
 // shared by the two parities of a head.  Protected (fp16) value rows are added
@@ -75,7 +99,6 @@ __device__ __forceinline__ uint64_t shl64(uint64_t v) {
   asm("" : "+v"(r));
   return r;
 }
-// byte B of w, times 8: one instruction with a sub-dword source select
 // byte B of w, times 8 (one instruction with a sub-dword source select)
 template <int B>
 __device__ __forceinline__ uint32_t byte_x8(uint32_t w) {

@@ -70,7 +70,7 @@ def test_decode_step_of_all_layers_captured_and_replayed():
 
 
 def test_large_residual_block_forked_inside_the_capture():
-    """A batch whose residual block is large enough to be forked onto the library's side
+    """A batch whose residual block is large enough to be forked onto the caller's side
     stream: the fork and join are captured with the rest and every replay equals the eager run."""
     w = synth.reduced(synth.WORKLOADS["c5_serving"], 8, B=32)
     print("[case] graph-decode forked residual block", flush=True)
